@@ -1,0 +1,207 @@
+/*
+ * ecoserve.h -- C ABI of the paged-attention hot path of an EcoServe instance
+ * (arXiv 2504.18154) for AMD MI355X (gfx950).
+ *
+ * An EcoServe instance alternates between phase-pure prefill-only and
+ * decode-only batches (Section 3.2, temporal disaggregation).  In both modes
+ * the device time of the attention layer is Eq. 2 of Section 2.1,
+ *     Attention(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V,
+ * evaluated over a KV cache (Section 2.1) that is organised in fixed-size
+ * blocks addressed through a per-sequence block table (Section 5, "KV cache
+ * management"), with grouped-query head sharing (Section 4.1).  This library
+ * is that path and nothing else: append new K/V rows to the paged cache,
+ * causal variable-length prefill attention, split-context decode attention.
+ *
+ * General rules
+ *   - Plain C.  No exception crosses the boundary; every call returns a
+ *     status code (ECOSERVE_OK == 0) and ecoserve_strerror() names it.
+ *   - "dev" pointers are device (HBM) addresses on the context's GPU, "host"
+ *     pointers are ordinary host memory.  Every buffer is caller-owned.  The
+ *     library allocates device memory only in ecoserve_create() and
+ *     ecoserve_set_option() and frees it in ecoserve_destroy().
+ *   - The three hot calls validate what the host can see (pointers, sizes,
+ *     alignment, limits) BEFORE launching anything, then enqueue their kernels
+ *     on the given HIP stream and return without synchronising.
+ *   - Contents of device arrays (block-table entries, lengths) are not
+ *     checked by the hot calls; out-of-range contents are undefined
+ *     behaviour.  ecoserve_debug_validate() checks them synchronously.
+ *   - One call handles one layer; callers loop over layers.
+ *   - Calls that share a context must be issued on one stream (or be ordered
+ *     by the caller): they share the context's split-context workspace.
+ *
+ * Notation (Table 1 of the paper, extended): B sequences in the batch, Hq
+ * query heads (M in the paper), Hkv key/value heads, G = Hq/Hkv, D per-head
+ * size, bs tokens per cache block.  Query head h uses K/V head h / G.
+ *
+ * Cache layout (fixed, one pool for K and one for V per layer; E = element
+ * type, x = 16 / sizeof(E) elements = one 16-byte unit):
+ *
+ *   k_cache : E[num_blocks][Hkv][D / x][bs][x]
+ *             (block, K/V head, 16-byte unit of the head vector, slot, element)
+ *   v_cache : E[num_blocks][Hkv][D][bs]
+ *             (block, K/V head, element of the head vector, slot)
+ *
+ * Each (block, head) is one contiguous piece of bs*D*sizeof(E) bytes (4 KiB
+ * for bf16, D = 128, bs = 16), so a wavefront streams it with fully coalesced
+ * 16-byte (K) and 8-byte (V) per-lane loads that land directly in the operand
+ * layout of the gfx950 matrix instructions.  ecoserve_k_cache_index() and
+ * ecoserve_v_cache_index() give the element offset of a logical coordinate.
+ */
+#ifndef ECOSERVE_H
+#define ECOSERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ecoserve_ctx ecoserve_ctx; /* opaque; owns a device workspace and timing events */
+
+enum {
+  ECOSERVE_OK = 0,
+  ECOSERVE_EINVAL = 1,       /* NULL / negative / inconsistent / misaligned argument */
+  ECOSERVE_EUNSUPPORTED = 2, /* valid in principle, not built (head size, block size, dtype) */
+  ECOSERVE_ENOMEM = 3,       /* device or host allocation failed */
+  ECOSERVE_EHIP = 4,         /* a HIP runtime call or kernel launch failed */
+  ECOSERVE_ECONTENT = 5      /* ecoserve_debug_validate(): device-resident contents are out of range */
+};
+
+enum { ECOSERVE_BF16 = 0, ECOSERVE_F32 = 1 };
+
+/* Head layout and paging of one layer's cache.
+ * Supported: block_size == 16; num_q_heads % num_kv_heads == 0 with
+ * G = Hq/Hkv <= 16; dtype BF16 with head_dim 128 (matrix-core kernels) or any
+ * head_dim that is a multiple of 8 up to 256 (plain kernels); dtype F32 with
+ * head_dim a multiple of 4 up to 256 (plain kernels). */
+typedef struct {
+  int32_t num_q_heads;
+  int32_t num_kv_heads;
+  int32_t head_dim;
+  int32_t block_size;
+  int32_t num_blocks;   /* physical blocks in one layer's pool */
+  int32_t dtype;        /* ECOSERVE_BF16 | ECOSERVE_F32: type of q, k, v, caches and out */
+  float softmax_scale;  /* 0 => 1/sqrt(head_dim), the scale of Eq. 2 */
+} ecoserve_layout;
+
+/* Tuning and test knobs for ecoserve_set_option(). */
+enum {
+  /* Tokens of context per decode split (multiple of 64, >= 64).  0 restores
+   * the built-in choice, which depends on B and max_ctx_len. */
+  ECOSERVE_OPT_DECODE_SPLIT_TOKENS = 1,
+  /* 1: use the plain (non matrix-core) kernels even where the fast ones apply. */
+  ECOSERVE_OPT_FORCE_PLAIN = 2,
+  /* 1: bracket the dominant kernel of each hot call with HIP events on the
+   * call's stream; read the sums with ecoserve_profile_read(). */
+  ECOSERVE_OPT_PROFILE = 3
+};
+
+enum { ECOSERVE_KERNEL_APPEND = 0, ECOSERVE_KERNEL_PREFILL = 1, ECOSERVE_KERNEL_DECODE = 2 };
+
+/* Create a context on `device` for batches of at most max_batch sequences whose
+ * block tables have at most max_blocks_per_seq entries per sequence.
+ * Allocates the decode workspace (split-context partial results).  On failure
+ * *out is NULL. */
+int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layout,
+                    int32_t max_batch, int32_t max_blocks_per_seq);
+
+/* Frees the workspace and events.  Synchronises the device first.  NULL is OK. */
+int ecoserve_destroy(ecoserve_ctx* ctx);
+
+/* Set a knob (see ECOSERVE_OPT_*).  May reallocate the workspace, so it
+ * synchronises the device; not for use between dependent hot calls in flight. */
+int ecoserve_set_option(ecoserve_ctx* ctx, int32_t option, int32_t value);
+
+/* Host-only helpers (no GPU needed). */
+const char* ecoserve_strerror(int status);
+/* Bytes of one layer's k_cache (== v_cache); 0 if the layout is invalid. */
+size_t ecoserve_cache_bytes(const ecoserve_layout* layout);
+/* Element offset of logical coordinate (blk, kv_head, slot, d) in k_cache / v_cache. */
+size_t ecoserve_k_cache_index(const ecoserve_layout* layout, int32_t blk, int32_t kv_head, int32_t slot, int32_t d);
+size_t ecoserve_v_cache_index(const ecoserve_layout* layout, int32_t blk, int32_t kv_head, int32_t slot, int32_t d);
+/* Bytes of device workspace the context currently holds. */
+size_t ecoserve_workspace_bytes(const ecoserve_ctx* ctx);
+
+/*
+ * KV-cache append (Section 2.1: the key and value embeddings of processed
+ * tokens are saved in memory and reused by later steps; Section 5: fixed-size
+ * blocks).  New token i of sequence b is stored at absolute position
+ * p = ctx_before[b] + i: block block_table[b][p / bs], slot p % bs.  Bit-exact
+ * copy.  Slots not addressed keep their contents.
+ *
+ *   k_cache, v_cache : dev, in/out, layout above, 16-byte aligned
+ *   k_new, v_new     : dev, E[T][Hkv][D], sequences packed back to back, 16-byte aligned
+ *   cu_q             : dev, int32[B+1], prefix sums of new-token counts, cu_q[0] = 0, cu_q[B] = T
+ *   ctx_before       : dev, int32[B], tokens of each sequence already cached
+ *   block_table      : dev, int32[B][bt_stride]; entries beyond a sequence's blocks are never read
+ *   B, T             : batch size and total new tokens (B <= max_batch); B == 0 or T == 0 is a no-op
+ *   max_new_len      : upper bound on any sequence's new-token count (sizes the launch)
+ *   stream           : hipStream_t (NULL = the default stream)
+ */
+int ecoserve_kv_append(ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
+                       const void* v_new, const int32_t* cu_q, const int32_t* ctx_before,
+                       const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
+                       int32_t max_new_len, void* stream);
+
+/*
+ * Prefill attention (Section 2.1, Eq. 2; prefill phase: all prompt tokens at
+ * once).  Causal, variable-length, grouped-query.  The new tokens' K/V must
+ * already be in the cache (call ecoserve_kv_append first).  New token i of
+ * sequence b sits at absolute position p = ctx_before[b] + i and attends to
+ * cached keys 0..p of its own sequence.
+ *
+ *   q           : dev, E[T][Hq][D], packed by sequence like k_new
+ *   k_cache, v_cache, cu_q, ctx_before, block_table, bt_stride, B, T : as in ecoserve_kv_append
+ *   out         : dev, E[T][Hq][D] (rounded to E with round-to-nearest-even)
+ *   lse         : dev, float[T][Hq] natural-log sum-exp of the scaled scores, or NULL
+ *   max_q_len   : upper bound on any sequence's new-token count (sizes the launch)
+ *   Sequences with zero new tokens are skipped.  B == 0 or T == 0 is a no-op.
+ */
+int ecoserve_attn_prefill(ecoserve_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
+                          int32_t bt_stride, void* out, float* lse, int32_t B, int32_t T,
+                          int32_t max_q_len, void* stream);
+
+/*
+ * Decode attention (Section 2.1, Eq. 2; decode phase: one new token per
+ * sequence attends to the whole cached context, which is what makes the phase
+ * memory-bound, Table 2).  The new token's K/V must already be appended;
+ * ctx_len[b] >= 1 counts it, and the query attends to keys 0..ctx_len[b]-1.
+ * The context of a sequence is split across workgroups; partial softmax
+ * states go through the context's workspace and are merged exactly.
+ *
+ *   q           : dev, E[B][Hq][D]
+ *   ctx_len     : dev, int32[B]
+ *   out         : dev, E[B][Hq][D];  lse : dev, float[B][Hq] or NULL
+ *   max_ctx_len : upper bound on ctx_len[] (sizes the launch);
+ *                 must be <= max_blocks_per_seq * block_size and <= bt_stride * block_size
+ */
+int ecoserve_attn_decode(ecoserve_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len,
+                         void* out, float* lse, int32_t B, int32_t max_ctx_len, void* stream);
+
+/*
+ * Synchronous check of device-resident arguments (tests and debugging; copies
+ * the arrays to the host).  Verifies cu_q monotone from 0 (if given), every
+ * length non-negative (decode: ctx_len >= 1 when cu_q == NULL), every block
+ * table entry that a call would dereference inside [0, num_blocks), and that
+ * no physical block is referenced twice.  `ctx_total[b]` is the number of
+ * tokens of sequence b the call would touch (ctx_before + new, or ctx_len).
+ * Returns ECOSERVE_ECONTENT on a violation.
+ */
+int ecoserve_debug_validate(ecoserve_ctx* ctx, const int32_t* cu_q, const int32_t* ctx_total,
+                            const int32_t* block_table, int32_t bt_stride, int32_t B);
+
+/*
+ * With ECOSERVE_OPT_PROFILE on: synchronise, then return the summed duration
+ * (milliseconds) and count of the dominant kernel of `kernel`
+ * (ECOSERVE_KERNEL_*) since the last ecoserve_profile_reset().
+ */
+int ecoserve_profile_read(ecoserve_ctx* ctx, int32_t kernel, double* ms_total, int64_t* launches);
+int ecoserve_profile_reset(ecoserve_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECOSERVE_H */
