@@ -1,0 +1,145 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/ecoserve.h"
+
+namespace eco {
+
+constexpr int kBlockSize = 16;        // tokens per cache block (the only supported value)
+constexpr int kMaxGroup = 16;         // largest supported Hq / Hkv
+constexpr int kMinSplitTokens = 64;   // smallest decode split
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct EventPair {
+  hipEvent_t start, stop;
+};
+
+}  // namespace eco
+
+struct ecoserve_ctx {
+  int device;
+  ecoserve_layout lay;
+  float scale;                 // resolved softmax scale
+  int32_t max_batch;
+  int32_t max_blocks_per_seq;
+  int num_cu;
+  // knobs
+  int32_t opt_split_tokens;    // 0 = automatic
+  int32_t opt_force_plain;
+  int32_t opt_profile;
+  // split-context workspace: unnormalised partial outputs and (max, sum) pairs
+  float* ws_acc;               // [max_batch][Hq][ws_splits][D]
+  float* ws_ml;                // [max_batch][Hq][ws_splits][2]
+  int32_t ws_splits;
+  size_t ws_bytes;
+  // profiling
+  std::vector<eco::EventPair> ev[3];
+  size_t ev_used[3];
+};
+
+namespace eco {
+
+// Arguments common to the attention launchers.
+struct AttnArgs {
+  const void* q;
+  const void* k_cache;
+  const void* v_cache;
+  const int32_t* block_table;
+  int32_t bt_stride;
+  void* out;
+  float* lse;
+  int32_t B;
+  int32_t Hq, Hkv, D;
+  int32_t dtype;
+  float scale_log2e;  // softmax scale times log2(e): scores live in the exp2 domain
+};
+
+// kv_append.hip
+hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
+                            const void* v_new, const int32_t* cu_q, const int32_t* ctx_before,
+                            const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
+                            int32_t max_new_len, hipStream_t s);
+
+// attn_plain.hip: any head size / dtype, no matrix cores
+hipError_t launch_prefill_plain(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
+                                hipStream_t s);
+hipError_t launch_decode_plain(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t n_split_max,
+                               float* ws_acc, float* ws_ml, int32_t ws_splits, hipStream_t s);
+// merges split partials into out/lse (shared by the plain and matrix-core decode paths)
+hipError_t launch_decode_merge(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, const float* ws_acc,
+                               const float* ws_ml, int32_t ws_splits, hipStream_t s);
+
+// attn_decode_mfma.hip: bf16, D = 128
+hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t n_split_max,
+                              float* ws_acc, float* ws_ml, int32_t ws_splits, hipStream_t s);
+
+// attn_prefill_mfma.hip: bf16, D = 128
+hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
+                               int32_t max_q_len, hipStream_t s);
+
+}  // namespace eco
+
+#if defined(__HIPCC__)
+namespace eco {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 bit pattern (NaN kept quiet)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename E>
+struct Elem;
+template <>
+struct Elem<uint16_t> {  // bf16 storage
+  static constexpr int X = 8;  // elements per 16-byte unit
+  static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
+  static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
+};
+template <>
+struct Elem<float> {
+  static constexpr int X = 4;
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+
+// Element offsets inside the paged pools (see include/ecoserve.h, "Cache layout").
+template <int X>
+__device__ __forceinline__ size_t k_index(int64_t blk, int g, int slot, int d, int Hkv, int D) {
+  return (((size_t)blk * Hkv + g) * (D / X) + (d / X)) * (kBlockSize * X) + (size_t)slot * X + (d % X);
+}
+__device__ __forceinline__ size_t v_index(int64_t blk, int g, int slot, int d, int Hkv, int D) {
+  return (((size_t)blk * Hkv + g) * D + d) * kBlockSize + slot;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+}  // namespace eco
+#endif

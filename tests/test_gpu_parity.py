@@ -1,0 +1,282 @@
+"""GPU parity tests: the HIP library, called through the C ABI, against the fp64 CPU oracle
+on the same seeded inputs, element by element.  Sizes here are ones the oracle finishes
+in seconds but that span several tiles, splits and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_18154_amd import workloads as wl
+from tests.parity_util import Layer, compare, compare_lse, dev_i32, say
+
+pytestmark = pytest.mark.gpu
+
+M30 = wl.ModelShape("30B-heads", 40, 8, 128, 1, "bf16")
+M70 = wl.ModelShape("70B-heads", 64, 8, 128, 1, "bf16")
+
+
+def _mk(model, q_len, ctx_before=None, seed=1, grow=0):
+    pb = wl.prefill_batch(model, q_len, seed, ctx_before=ctx_before, grow=grow)
+    layer = Layer(model, pb.num_blocks, max_batch=max(pb.B, 1), max_blocks_per_seq=pb.block_table.shape[1])
+    return pb, layer
+
+
+def _qkv(model, T, seed, qscale=1.0, vscale=1.0):
+    q = wl.randn((T, model.Hq, model.D), model.dtype, seed, scale=qscale)
+    k = wl.randn((T, model.Hkv, model.D), model.dtype, seed + 1)
+    v = wl.randn((T, model.Hkv, model.D), model.dtype, seed + 2, scale=vscale)
+    return q, k, v
+
+
+def test_config1_tiny_padg_cycle_fp32():
+    """Config 1: prefill-only batch (37 and 100 tokens) then 8 decode-only steps, fp32,
+    full oracle at every step, cache compared bit for bit after every append."""
+    say("config 1: tiny PaDG cycle fp32")
+    pb = wl.config1_tiny()
+    model = pb.model
+    layer = Layer(model, pb.num_blocks, 2, pb.block_table.shape[1])
+    q, k, v = _qkv(model, pb.T, wl.config_seed(1))
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    compare("prefill", out, ref, "f32")
+    compare_lse("prefill", lse, ref_lse, "f32")
+    ctx = pb.q_len.copy()
+    ones = wl.cu_from_lengths([1, 1])
+    for step in range(8):
+        q, k, v = _qkv(model, 2, wl.config_seed(1) + 10 * (step + 1))
+        layer.append(k, v, ones, ctx, pb.block_table)
+        ctx = ctx + 1
+        layer.assert_cache_bit_exact()
+        out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+        compare(f"decode step {step}", out, ref, "f32")
+        compare_lse(f"decode step {step}", lse, ref_lse, "f32")
+    layer.close()
+
+
+@pytest.mark.parametrize("model", [M30, M70], ids=["G5", "G8"])
+def test_bf16_prefill_ragged_lengths(model):
+    q_len = [1, 15, 16, 17, 127, 128, 129, 300, 0, 64, 513]
+    say(f"bf16 prefill ragged {model.name} {q_len}")
+    pb, layer = _mk(model, q_len, seed=5)
+    q, k, v = _qkv(model, pb.T, 50)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    compare("prefill", out, ref, "bf16")
+    compare_lse("prefill", lse, ref_lse, "bf16")
+    layer.close()
+
+
+def test_bf16_prefill_with_cached_prefix():
+    """Second chunk of a prompt: queries sit at ctx_before + i and see the prefix too."""
+    model = M30
+    first, second = [70, 16, 200, 33], [90, 129, 1, 31]
+    total = [a + b for a, b in zip(first, second)]
+    say(f"bf16 prefill with prefix {first} + {second}")
+    pb, layer = _mk(model, total, seed=6)
+    cu1, cu2 = wl.cu_from_lengths(first), wl.cu_from_lengths(second)
+    zero = np.zeros(4, dtype=np.int32)
+    q1, k1, v1 = _qkv(model, int(cu1[-1]), 60)
+    layer.append(k1, v1, cu1, zero, pb.block_table)
+    q2, k2, v2 = _qkv(model, int(cu2[-1]), 70)
+    cb = np.asarray(first, dtype=np.int32)
+    layer.append(k2, v2, cu2, cb, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q2, cu2, cb, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q2, cu2, cb, pb.block_table)
+    compare("prefill chunk 2", out, ref, "bf16")
+    compare_lse("prefill chunk 2", lse, ref_lse, "bf16")
+    layer.close()
+
+
+DECODE_LENS = [1, 15, 16, 17, 63, 64, 65, 100, 513, 1000, 2047, 2048, 2049, 3000]
+
+
+@pytest.mark.parametrize("model", [M30, M70], ids=["G5", "G8"])
+def test_bf16_decode_split_plans(model):
+    """Decode over ragged contexts with the automatic plan and forced split sizes
+    (one split, many splits); every plan must meet the tolerance, the cache is shared."""
+    from paper_2504_18154_amd import binding
+    say(f"bf16 decode split plans {model.name}")
+    pb, layer = _mk(model, DECODE_LENS, seed=7)
+    T = pb.T
+    _, k, v = _qkv(model, T, 80)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    B = pb.B
+    q = wl.randn((B, model.Hq, model.D), "bf16", 81)
+    ctx = pb.q_len
+    ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+    outs = {}
+    for split in (0, 64, 128, 448, 1024, 4096):
+        layer.ctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, split)
+        out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+        compare(f"decode split={split}", out, ref, "bf16")
+        compare_lse(f"decode split={split}", lse, ref_lse, "bf16")
+        out2, _ = layer.decode_gpu(q, pb.block_table, ctx)
+        assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "decode is not run-to-run deterministic"
+        outs[split] = out
+    layer.close()
+
+
+def test_bf16_decode_after_growth_steps():
+    """Decode-only phase: several steps, each appending one token per sequence (crossing
+    block boundaries) before attending."""
+    model = M30
+    lens = [14, 15, 16, 31, 47, 250, 1023]
+    say(f"bf16 decode growth {lens}")
+    pb, layer = _mk(model, lens, seed=8, grow=4)
+    _, k, v = _qkv(model, pb.T, 90)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    ctx = pb.q_len.copy()
+    ones = wl.cu_from_lengths([1] * pb.B)
+    for step in range(4):
+        q, k, v = _qkv(model, pb.B, 100 + 10 * step)
+        layer.append(k, v, ones, ctx, pb.block_table, max_new_len=1)
+        ctx = ctx + 1
+        layer.assert_cache_bit_exact()
+        out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+        compare(f"decode step {step}", out, ref, "bf16")
+        compare_lse(f"decode step {step}", lse, ref_lse, "bf16")
+    layer.close()
+
+
+@pytest.mark.parametrize("model", [M30, wl.ModelShape("d64", 8, 2, 64, 1, "bf16"),
+                                   wl.ModelShape("f32-d128", 6, 3, 128, 1, "f32")], ids=["bf16-d128", "bf16-d64", "f32-d128"])
+def test_plain_kernels(model):
+    """The plain (non matrix-core) kernels on shapes the fast path also/never covers."""
+    from paper_2504_18154_amd import binding
+    lens = [1, 17, 64, 130, 333]
+    say(f"plain kernels {model.name}")
+    pb, layer = _mk(model, lens, seed=9)
+    layer.ctx.set_option(binding.OPT_FORCE_PLAIN, 1)
+    q, k, v = _qkv(model, pb.T, 110)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    compare("prefill", out, ref, model.dtype)
+    compare_lse("prefill", lse, ref_lse, model.dtype)
+    qd = wl.randn((pb.B, model.Hq, model.D), model.dtype, 111)
+    ref, ref_lse = layer.decode_oracle(qd, pb.block_table, pb.q_len)
+    for split in (0, 64, 4096):
+        layer.ctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, split)
+        out, lse = layer.decode_gpu(qd, pb.block_table, pb.q_len)
+        compare(f"decode split={split}", out, ref, model.dtype)
+        compare_lse(f"decode split={split}", lse, ref_lse, model.dtype)
+    layer.close()
+
+
+def test_bf16_peaky_softmax():
+    """Queries scaled x8: near one-hot weights exercise max tracking and rescaling.  Values
+    are scaled x0.25 so that outputs stay below 2, where a bf16 output ulp is under the
+    max-abs bound."""
+    model = M30
+    lens = [200, 1000, 77]
+    say("bf16 peaky softmax")
+    pb, layer = _mk(model, lens, seed=10)
+    q, k, v = _qkv(model, pb.T, 120, qscale=8.0, vscale=0.25)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    compare("prefill", out, ref, "bf16")
+    last = pb.cu_q[1:] - 1
+    qd = q[torch.as_tensor(last, dtype=torch.long)]
+    out_d, _ = layer.decode_gpu(qd, pb.block_table, pb.q_len)
+    compare("decode", out_d, ref[last], "bf16")
+    layer.close()
+
+
+def test_single_token_context_is_exact():
+    """L = 1: the only weight is 1, so the output must equal V bit for bit (both kernels)."""
+    model = M70
+    say("single-token contexts")
+    pb, layer = _mk(model, [1] * 5, seed=11)
+    q, k, v = _qkv(model, 5, 130, qscale=4.0)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    expect = v.cuda().repeat_interleave(model.G, dim=1).view(torch.int16)
+    out_d, lse = layer.decode_gpu(q, pb.block_table, pb.q_len)
+    out_p, _ = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    assert torch.equal(out_d.view(torch.int16), expect)
+    assert torch.equal(out_p.view(torch.int16), expect)
+    layer.close()
+
+
+def test_unwritten_slots_and_unused_blocks_are_never_read_or_written():
+    """Pools start as NaN sentinels.  Outputs must be finite (no stray read reaches them)
+    and every unaddressed slot must keep its sentinel (covered by the whole-pool compare)."""
+    model = M30
+    lens = [3, 18, 50, 129, 1000]
+    say("poison test")
+    pb, layer = _mk(model, lens, seed=12, grow=20)   # spare table entries stay -1
+    q, k, v = _qkv(model, pb.T, 140)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, _ = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    assert torch.isfinite(out.float()).all()
+    qd = wl.randn((pb.B, model.Hq, model.D), "bf16", 141)
+    out_d, _ = layer.decode_gpu(qd, pb.block_table, pb.q_len)
+    assert torch.isfinite(out_d.float()).all()
+    ref, _ = layer.decode_oracle(qd, pb.block_table, pb.q_len)
+    compare("decode", out_d, ref, "bf16")
+    layer.close()
+
+
+def test_empty_batches_and_host_side_errors():
+    from paper_2504_18154_amd import binding
+    model = M30
+    say("empty batches / error codes")
+    pb, layer = _mk(model, [40, 0, 7], seed=13)
+    c = layer.ctx
+    q, k, v = _qkv(model, pb.T, 150)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    cu, cb, bt = dev_i32(pb.cu_q), dev_i32(pb.ctx_before), dev_i32(pb.block_table)
+    # T == 0 and B == 0 are no-ops
+    empty = torch.empty((0, model.Hkv, model.D), dtype=torch.bfloat16, device="cuda")
+    c.kv_append(layer.kc, layer.vc, empty, empty, cu, cb, bt)
+    c.attn_decode(qd[:0], layer.kc, layer.vc, bt, cb[:0], qd[:0], 1)
+    # batch larger than the context was created for
+    with pytest.raises(binding.EcoserveError) as e:
+        big = dev_i32(np.zeros(8))
+        c.attn_decode(qd[:8], layer.kc, layer.vc, bt, big, qd[:8].clone(), 16)
+    assert e.value.status == binding.EINVAL
+    # max_ctx_len beyond the block table
+    with pytest.raises(binding.EcoserveError) as e:
+        c.attn_decode(qd[:3], layer.kc, layer.vc, bt, cb, qd[:3].clone(), 16 * pb.block_table.shape[1] + 1)
+    assert e.value.status == binding.EINVAL
+    # misaligned pointer
+    with pytest.raises(binding.EcoserveError) as e:
+        mis = torch.empty(qd.numel() + 8, dtype=torch.bfloat16, device="cuda")[1:1 + qd.numel()].view_as(qd)
+        c.attn_prefill(mis, layer.kc, layer.vc, cu, cb, bt, torch.empty_like(qd))
+    assert e.value.status == binding.EINVAL
+    # device-resident contents: the debug validator sees what the hot calls do not check
+    total = dev_i32(pb.q_len)
+    assert c.debug_validate(cu, total, bt) == binding.OK
+    bad = pb.block_table.copy(); bad[0, 1] = pb.num_blocks
+    assert c.debug_validate(cu, total, dev_i32(bad)) == binding.ECONTENT
+    dup = pb.block_table.copy(); dup[2, 0] = dup[0, 0]
+    assert c.debug_validate(cu, total, dev_i32(dup)) == binding.ECONTENT
+    assert c.debug_validate(None, dev_i32([40, 0, 7]), bt) == binding.ECONTENT   # decode needs ctx_len >= 1
+    layer.close()
+
+
+def test_profile_events_report_kernel_time():
+    from paper_2504_18154_amd import binding
+    model = M30
+    pb, layer = _mk(model, [300, 500], seed=14)
+    q, k, v = _qkv(model, pb.T, 160)
+    layer.ctx.set_option(binding.OPT_PROFILE, 1)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    for _ in range(3):
+        layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ms, n = layer.ctx.profile_read(binding.KERNEL_PREFILL)
+    assert n == 3 and 0 < ms < 1000
+    ms, n = layer.ctx.profile_read(binding.KERNEL_APPEND)
+    assert n == 1 and ms > 0
+    layer.ctx.profile_reset()
+    assert layer.ctx.profile_read(binding.KERNEL_PREFILL) == (0.0, 0)
+    layer.close()
