@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+
+One "step" is one pass of the whole hot path over one phase-pure batch pair of the
+30B-scale model (40 query heads, 8 K/V heads, head size 128, block size 16, 64 layers,
+bf16), with every input resident in HBM before the timed region starts:
+
+  * prefill-only batch (BASELINE config index 2): 16 prompts, lengths lognormal(mean 1024)
+    clipped to [128, 4096]; per layer kv_append of all prompt tokens, then causal prefill
+    attention over the paged cache;
+  * decode-only batch (BASELINE config index 1): 128 resident sequences, contexts uniform in
+    [512, 4096], physical blocks randomly permuted; per layer kv_append of one token per
+    sequence, then split-context decode attention.  64 independent layer caches.
+
+It prints ONE JSON line.  `value` is the decode phase's algorithmic HBM traffic rate (GB/s),
+the headline metric; the prefill phase's causal TFLOP/s and the append rates ride along.
+`roofline` is for the dominant kernel (decode partial attention): algorithmic bytes per
+launch / its average launch duration, measured with HIP events recorded by the library on
+the launch stream around every launch inside the timed region.  `cpu_baseline` is the fp64
+oracle on the host cores, on one layer of the decode batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalid as a result)")
+    ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split size (tuning)")
+    ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
+                    help="run only one phase (profiling runs; the default is the full step)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no cross-GPU exchange step); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2504_18154_amd import accounting as acc
+    from paper_2504_18154_amd import binding, build
+    from paper_2504_18154_amd import workloads as wl
+
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda", 0)
+    model = wl.M30B
+    layers = args.layers or model.layers
+    do_dec = args.phase in ("both", "decode")
+    do_pre = args.phase in ("both", "prefill")
+
+    def i32(a):
+        return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=dev)
+
+    def fill_randn_(t: torch.Tensor, seed: int):
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        chunk = 1 << 26
+        flat = t.view(-1)
+        for o in range(0, flat.numel(), chunk):
+            n = min(chunk, flat.numel() - o)
+            flat[o:o + n] = torch.randn(n, generator=g, device=dev, dtype=torch.float32).to(t.dtype)
+
+    # ---------------- decode-only batch (config index 1) ---------------------------------
+    db = wl.config2_decode_30b()
+    dctx = binding.Context(model.Hq, model.Hkv, model.D, db.num_blocks, "bf16", db.B, db.block_table.shape[1])
+    if args.split_tokens:
+        dctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, args.split_tokens)
+    pool_elems = db.num_blocks * model.Hkv * model.bs * model.D
+    d_bt, d_len = i32(db.block_table), i32(db.ctx_len)
+    d_before = i32(db.ctx_len - 1)
+    d_cu = i32(np.arange(db.B + 1))
+    d_pools = []
+    stream_k = stream_v = None
+    if do_dec:
+        for l in range(layers):
+            if l == 0:
+                # layer 0 is built through kv_append from a token stream the oracle can replay
+                kc, vc = dctx.new_cache()
+                T0 = int(db.ctx_len.sum())
+                stream_k = wl.randn((T0, model.Hkv, model.D), "bf16", db.seed + 1, device=dev)
+                stream_v = wl.randn((T0, model.Hkv, model.D), "bf16", db.seed + 2, device=dev)
+                dctx.kv_append(kc, vc, stream_k, stream_v, i32(wl.cu_from_lengths(db.ctx_len)),
+                               i32(np.zeros(db.B)), d_bt)
+            else:
+                kc = torch.empty(pool_elems, dtype=torch.bfloat16, device=dev)
+                vc = torch.empty(pool_elems, dtype=torch.bfloat16, device=dev)
+                fill_randn_(kc, db.seed + 10 * l)
+                fill_randn_(vc, db.seed + 10 * l + 1)
+            d_pools.append((kc, vc))
+    d_q = wl.randn((db.B, model.Hq, model.D), "bf16", db.seed + 3, device=dev)
+    d_knew = wl.randn((db.B, model.Hkv, model.D), "bf16", db.seed + 4, device=dev)
+    d_vnew = wl.randn((db.B, model.Hkv, model.D), "bf16", db.seed + 5, device=dev)
+    if do_dec:
+        # the new token of layer 0 is the last token of its stream, so the cache stays replayable
+        last = torch.as_tensor(np.cumsum(db.ctx_len) - 1, device=dev, dtype=torch.long)
+        d_knew0, d_vnew0 = stream_k[last].contiguous(), stream_v[last].contiguous()
+    d_out = torch.empty((layers, db.B, model.Hq, model.D), dtype=torch.bfloat16, device=dev)
+
+    # ---------------- prefill-only batch (config index 2) --------------------------------
+    pb = wl.config3_prefill_30b()
+    pctx = binding.Context(model.Hq, model.Hkv, model.D, pb.num_blocks, "bf16", pb.B, pb.block_table.shape[1])
+    p_bt, p_cu, p_before = i32(pb.block_table), i32(pb.cu_q), i32(pb.ctx_before)
+    p_pools = [pctx.new_cache(fill_bits=0) for _ in range(layers)] if do_pre else []
+    p_q = wl.randn((pb.T, model.Hq, model.D), "bf16", pb.seed + 3, device=dev)
+    p_k = wl.randn((pb.T, model.Hkv, model.D), "bf16", pb.seed + 4, device=dev)
+    p_v = wl.randn((pb.T, model.Hkv, model.D), "bf16", pb.seed + 5, device=dev)
+    p_out = torch.empty_like(p_q)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(timers=None):
+        t = [ev() for _ in range(3)]
+        t[0].record()
+        if do_pre:
+            for l in range(layers):
+                kc, vc = p_pools[l]
+                pctx.kv_append(kc, vc, p_k, p_v, p_cu, p_before, p_bt, max_new_len=pb.max_q_len)
+                pctx.attn_prefill(p_q, kc, vc, p_cu, p_before, p_bt, p_out, max_q_len=pb.max_q_len)
+        t[1].record()
+        if do_dec:
+            for l in range(layers):
+                kc, vc = d_pools[l]
+                kn, vn = (d_knew0, d_vnew0) if l == 0 else (d_knew, d_vnew)
+                dctx.kv_append(kc, vc, kn, vn, d_cu, d_before, d_bt, max_new_len=1)
+                dctx.attn_decode(d_q, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
+        t[2].record()
+        if timers is not None:
+            timers.append(t)
+
+    for _ in range(args.warmup):
+        step()
+    for c in (dctx, pctx):
+        c.set_option(binding.OPT_PROFILE, 1)
+        c.profile_reset()
+    timers = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timers)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    pre_ms = sum(t[0].elapsed_time(t[1]) for t in timers) / args.steps
+    dec_ms = sum(t[1].elapsed_time(t[2]) for t in timers) / args.steps
+    k_dec_ms, k_dec_n = dctx.profile_read(binding.KERNEL_DECODE)
+    k_dapp_ms, k_dapp_n = dctx.profile_read(binding.KERNEL_APPEND)
+    k_pre_ms, k_pre_n = pctx.profile_read(binding.KERNEL_PREFILL)
+    k_papp_ms, k_papp_n = pctx.profile_read(binding.KERNEL_APPEND)
+
+    # ---------------- algorithmic work --------------------------------------------------
+    dec_bytes_layer = acc.decode_bytes(db.ctx_len, model.Hq, model.Hkv, model.D, model.bs)
+    dec_app_bytes_layer = acc.append_bytes(db.B, model.Hkv, model.D)
+    pre_flops_layer = acc.prefill_flops_causal(pb.q_len, model.Hq, model.D)
+    pre_app_bytes_layer = acc.append_bytes(pb.T, model.Hkv, model.D)
+
+    def rate(x, ms):
+        return x / (ms * 1e-3) if ms and ms > 0 else None
+
+    res = {
+        "metric": "decode attn HBM GB/s + prefill attn TFLOP/s, % of MI355X roofline",
+        "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": "30B-scale PaDG step: prefill-only batch (16 prompts, lognormal mean 1024 in [128,4096]) "
+                        "then decode-only batch (128 seqs, ctx U[512,4096]); 40 q heads / 8 kv heads / D 128 / "
+                        "block 16; append + attention per layer",
+            "layers": layers, "phase": args.phase,
+            "decode_batch": db.B, "decode_ctx_tokens": int(db.ctx_len.sum()),
+            "prefill_prompts": pb.B, "prefill_tokens": pb.T, "prefill_lengths": [int(x) for x in pb.q_len],
+        },
+    }
+    if do_dec:
+        # phase time includes the one-token appends and the merge kernels: whole decode phase
+        res["value"] = rate(dec_bytes_layer * layers, dec_ms) / 1e9
+        res["decode"] = {
+            "ms_per_layer": dec_ms / layers, "phase_ms": dec_ms, "GBps": res["value"],
+            "frac_of_hbm_peak": res["value"] / acc.PEAK_HBM_GBPS,
+            "append_us_per_layer": 1e3 * k_dapp_ms / max(k_dapp_n, 1),
+        }
+        avg_ms = k_dec_ms / max(k_dec_n, 1)
+        a = rate(dec_bytes_layer, avg_ms) / 1e9
+        res["roofline"] = {"kernel": "decode_mfma_kernel", "bound": "hbm", "achieved": a, "peak": acc.PEAK_HBM_GBPS,
+                           "unit": "GB/s", "frac": a / acc.PEAK_HBM_GBPS, "traffic": None,
+                           "avg_launch_us": avg_ms * 1e3, "launches": k_dec_n,
+                           "algorithmic_bytes_per_launch": dec_bytes_layer}
+    if do_pre:
+        tf = rate(pre_flops_layer * layers, pre_ms) / 1e12
+        avg_ms = k_pre_ms / max(k_pre_n, 1)
+        ktf = rate(pre_flops_layer, avg_ms) / 1e12
+        app_ms = k_papp_ms / max(k_papp_n, 1)
+        res["prefill"] = {
+            "value": tf, "unit": "TFLOP/s", "ms_per_layer": pre_ms / layers, "phase_ms": pre_ms,
+            "frac_of_bf16_peak": tf / acc.PEAK_BF16_TFLOPS,
+            "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": ktf,
+                         "peak": acc.PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ktf / acc.PEAK_BF16_TFLOPS,
+                         "traffic": None, "avg_launch_us": avg_ms * 1e3, "launches": k_pre_n,
+                         "algorithmic_flops_per_launch": pre_flops_layer},
+            "append": {"GBps": rate(pre_app_bytes_layer, app_ms) / 1e9, "avg_launch_us": app_ms * 1e3,
+                       "frac_of_hbm_peak": rate(pre_app_bytes_layer, app_ms) / 1e9 / acc.PEAK_HBM_GBPS},
+        }
+        if not do_dec:
+            res["value"], res["unit"] = tf, "TFLOP/s"
+
+    # ---------------- CPU baseline: the oracle on one decode layer ------------------------
+    if do_dec and not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        shape = orc.Shape(model.Hq, model.Hkv, model.D, model.bs, db.num_blocks, orc.BF16)
+        okc, ovc = orc.new_cache(shape)
+        orc.kv_append(shape, okc, ovc, wl.to_bits(stream_k), wl.to_bits(stream_v), wl.cu_from_lengths(db.ctx_len),
+                      np.zeros(db.B, dtype=np.int32), db.block_table)
+        qh = wl.to_bits(d_q)
+        t0 = time.perf_counter()
+        ref, _ = orc.attn_decode(shape, qh, okc, ovc, db.block_table, db.ctx_len)
+        cpu_s = time.perf_counter() - t0
+        err = np.abs(d_out[0].double().cpu().numpy() - ref)
+        res["cpu_baseline"] = {
+            "value": dec_bytes_layer / cpu_s / 1e9, "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"one full layer of the decode batch (128 seqs, {int(db.ctx_len.sum())} cached tokens), "
+                      f"fp64, {cpu_s:.2f} s",
+            "seconds": cpu_s,
+            "gpu_vs_oracle_layer0_max_abs": float(err.max()), "gpu_vs_oracle_layer0_mean_abs": float(err.mean()),
+        }
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
