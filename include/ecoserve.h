@@ -87,7 +87,7 @@ typedef struct {
 
 /* Tuning and test knobs for ecoserve_set_option(). */
 enum {
-  /* Tokens of context per decode split (multiple of 64, >= 64).  0 restores
+  /* Tokens of context per decode split (multiple of 64, 64..4096).  0 restores
    * the built-in choice, which depends on B and max_ctx_len. */
   ECOSERVE_OPT_DECODE_SPLIT_TOKENS = 1,
   /* 1: use the plain (non matrix-core) kernels even where the fast ones apply. */

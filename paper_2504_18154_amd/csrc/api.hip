@@ -42,7 +42,7 @@ int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
 // and shorten the tail; larger ones write fewer partial states.
 int32_t plan_split_tokens(const ecoserve_ctx* c, int32_t B, int32_t max_ctx_len) {
   if (c->opt_split_tokens > 0) return c->opt_split_tokens;
-  const int64_t heads = use_mfma(c) ? c->lay.num_kv_heads : c->lay.num_q_heads;
+  const int64_t heads = c->lay.num_q_heads;
   const int64_t want = 8LL * c->num_cu;  // workgroups needed to fill the chip a few times over
   int32_t st = 512;
   while (st > kMinSplitTokens && (int64_t)B * heads * ceil_div(max_ctx_len, st) < want) st >>= 1;
@@ -50,12 +50,15 @@ int32_t plan_split_tokens(const ecoserve_ctx* c, int32_t B, int32_t max_ctx_len)
 }
 
 int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
-  const int32_t splits = ceil_div(c->max_blocks_per_seq * kBlockSize, min_split_tokens);
+  // a sequence of n blocks cut into chunks of >= c blocks at arbitrary offsets has at most n/c + 2 pieces
+  const int32_t splits = ceil_div(c->max_blocks_per_seq * kBlockSize, min_split_tokens) + 2;
   if (c->ws_acc && splits <= c->ws_splits) return ECOSERVE_OK;
   if (c->ws_acc) (void)hipFree(c->ws_acc);
   if (c->ws_ml) (void)hipFree(c->ws_ml);
+  if (c->ws_meta) (void)hipFree(c->ws_meta);
   c->ws_acc = nullptr;
   c->ws_ml = nullptr;
+  c->ws_meta = nullptr;
   c->ws_splits = 0;
   c->ws_bytes = 0;
   const size_t slots = (size_t)c->max_batch * c->lay.num_q_heads * splits;
@@ -63,14 +66,18 @@ int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
   const size_t ml_bytes = slots * 2 * sizeof(float);
   if (slots == 0) return ECOSERVE_OK;
   if (hipMalloc(&c->ws_acc, acc_bytes) != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_ENOMEM; }
-  if (hipMalloc(&c->ws_ml, ml_bytes) != hipSuccess) {
+  const size_t meta_bytes = ((size_t)c->max_batch + 3) * sizeof(int32_t);
+  if (hipMalloc(&c->ws_ml, ml_bytes) != hipSuccess || hipMalloc(&c->ws_meta, meta_bytes) != hipSuccess) {
     (void)hipGetLastError();
     (void)hipFree(c->ws_acc);
+    if (c->ws_ml) (void)hipFree(c->ws_ml);
     c->ws_acc = nullptr;
+    c->ws_ml = nullptr;
+    c->ws_meta = nullptr;
     return ECOSERVE_ENOMEM;
   }
   c->ws_splits = splits;
-  c->ws_bytes = acc_bytes + ml_bytes;
+  c->ws_bytes = acc_bytes + ml_bytes + meta_bytes;
   return ECOSERVE_OK;
 }
 
@@ -151,7 +158,7 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   *out = nullptr;
   int st;
   if (!layout_ok(layout, &st)) return st;
-  if (max_batch <= 0 || max_blocks_per_seq <= 0 || device < 0) return ECOSERVE_EINVAL;
+  if (max_batch <= 0 || max_batch > kMaxBatch || max_blocks_per_seq <= 0 || device < 0) return ECOSERVE_EINVAL;
   if ((int64_t)max_blocks_per_seq * kBlockSize > 0x7fffffffLL) return ECOSERVE_EINVAL;
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_EHIP; }
@@ -173,6 +180,7 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   c->opt_profile = 0;
   c->ws_acc = nullptr;
   c->ws_ml = nullptr;
+  c->ws_meta = nullptr;
   c->ws_splits = 0;
   c->ws_bytes = 0;
   for (int i = 0; i < 3; ++i) c->ev_used[i] = 0;
@@ -189,6 +197,7 @@ int ecoserve_destroy(ecoserve_ctx* c) {
   if (!guard.ok || hipDeviceSynchronize() != hipSuccess) rc = ECOSERVE_EHIP;
   if (c->ws_acc) (void)hipFree(c->ws_acc);
   if (c->ws_ml) (void)hipFree(c->ws_ml);
+  if (c->ws_meta) (void)hipFree(c->ws_meta);
   for (int i = 0; i < 3; ++i)
     for (EventPair& e : c->ev[i]) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
   delete c;
@@ -199,7 +208,7 @@ int ecoserve_set_option(ecoserve_ctx* c, int32_t option, int32_t value) {
   if (!c) return ECOSERVE_EINVAL;
   switch (option) {
     case ECOSERVE_OPT_DECODE_SPLIT_TOKENS:
-      if (value != 0 && (value < kMinSplitTokens || value % 64 != 0)) return ECOSERVE_EINVAL;
+      if (value != 0 && (value < kMinSplitTokens || value > kMaxSplitTokens || value % 64 != 0)) return ECOSERVE_EINVAL;
       c->opt_split_tokens = value;
       return ECOSERVE_OK;
     case ECOSERVE_OPT_FORCE_PLAIN:
@@ -288,16 +297,23 @@ int ecoserve_attn_decode(ecoserve_ctx* c, const void* q, const void* k_cache, co
   if (!guard.ok) return ECOSERVE_EHIP;
   hipStream_t s = (hipStream_t)stream;
   const AttnArgs a = make_args(c, q, k_cache, v_cache, block_table, bt_stride, out, lse, B);
+  hipError_t e;
+  if (use_mfma(c)) {
+    {
+      ProfileScope prof(c, ECOSERVE_KERNEL_DECODE, s);
+      e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len, c->num_cu, c->ws_acc, c->ws_ml, c->ws_meta,
+                             c->ws_splits, s);
+    }
+    if (e != hipSuccess) return ECOSERVE_EHIP;
+    e = launch_decode_mfma_merge(a, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, s);
+    return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
+  }
   const int32_t split_tokens = plan_split_tokens(c, B, max_ctx_len);
   const int32_t n_split_max = ceil_div(max_ctx_len, split_tokens);
   if (n_split_max > c->ws_splits) return ECOSERVE_EINVAL;  // cannot happen for split_tokens >= kMinSplitTokens
-  hipError_t e;
   {
     ProfileScope prof(c, ECOSERVE_KERNEL_DECODE, s);
-    if (use_mfma(c))
-      e = launch_decode_mfma(a, ctx_len, split_tokens, n_split_max, c->ws_acc, c->ws_ml, c->ws_splits, s);
-    else
-      e = launch_decode_plain(a, ctx_len, split_tokens, n_split_max, c->ws_acc, c->ws_ml, c->ws_splits, s);
+    e = launch_decode_plain(a, ctx_len, split_tokens, n_split_max, c->ws_acc, c->ws_ml, c->ws_splits, s);
   }
   if (e != hipSuccess) return ECOSERVE_EHIP;
   if (n_split_max > 1) {

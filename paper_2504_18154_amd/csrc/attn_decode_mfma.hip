@@ -2,24 +2,31 @@
 //
 // Eq. 2 of Section 2.1 for one new token per sequence against the whole cached context:
 // the memory-bound phase of Table 2 (every cached K and V byte is read once per step,
-// arithmetic intensity = the GQA group size).  The kernel is therefore organised around
-// the HBM stream, and the matrix cores are used only so that arithmetic never gets in
-// its way:
+// arithmetic intensity = the GQA group size).  The kernel is organised around the HBM
+// stream; the matrix cores are used only so that arithmetic never gets in its way.
 //
-//   * grid (split, K/V head, sequence); a workgroup of 4 wavefronts owns one context
-//     slice of one (sequence, K/V head) and serves all G query heads of the group from
-//     one pass over the slice's K/V bytes;
-//   * each wavefront streams whole 16-token cache blocks (4 KiB of K, 4 KiB of V) with
-//     fully coalesced per-lane loads that land directly in MFMA operand layout - no LDS
-//     staging, no barriers in the loop, next block prefetched into registers;
-//   * scores S^T[token][head] = K . Q^T with v_mfma_f32_16x16x32_bf16 (heads padded to the
-//     16 columns), online softmax per column in the exp2 domain, the 4x(16 lanes) partial
-//     maxima combined with wavefront shuffles, and O^T[d][head] += V^T . P^T with
-//     v_mfma_f32_16x16x16_bf16: the accumulator layout of the first product is already
-//     the B-operand layout of the second, so P never leaves registers;
-//   * the 4 wavefronts' states are merged through LDS; with one slice per sequence the
-//     result is final, otherwise (m, l, unnormalised o) go to the workspace for the merge
-//     kernel.
+// Work decomposition ("flat" split-context).  A unit of work is one 16-token cache block
+// of one (sequence, K/V head): 4 KiB of K and 4 KiB of V serving all G query heads of the
+// group.  Units are numbered sequence-major, then K/V head, then logical block, and the
+// numbering is cut into equal chunks of C units, one chunk per wavefront of a persistent
+// grid (2 workgroups of 4 wavefronts per CU).  Context lengths live on the device, so every
+// workgroup derives the numbering itself from a prefix sum over the batch (a few hundred
+// integers).  All wavefronts therefore stream the same number of bytes whatever the mix of
+// context lengths, start together and finish together.  A chunk may cover the tail of one
+// (sequence, head), several whole ones and the head of another; each covered piece yields
+// one partial softmax state.
+//
+// Per piece, the wavefront streams whole cache blocks with fully coalesced per-lane loads
+// that land directly in MFMA operand layout - no LDS staging, no barriers, a register
+// pipeline three blocks deep, physical block ids prefetched 64 at a time into one VGPR:
+//   scores  S^T[token][head] = K . Q^T   v_mfma_f32_16x16x32_bf16 (heads padded to 16 columns)
+//   online softmax per column in the exp2 domain; the four 16-lane groups hold different
+//   tokens of the same head, their maxima are combined with wavefront shuffles
+//   values  O^T[d][head] += V^T . P^T    v_mfma_f32_16x16x16_bf16
+// The accumulator layout of the first product is already the B-operand layout of the
+// second, so P never leaves registers.  A piece that is a whole (sequence, head) writes the
+// final output; otherwise (m, l, unnormalised o) go to the workspace and a small merge
+// kernel combines them exactly.
 //
 // Lane layouts relied upon (lane = 16*quad + col):
 //   16x16x32:  A[row=col][k = 8*quad .. 8*quad+7],  B[k = 8*quad..+7][col],
@@ -44,150 +51,259 @@ __device__ __forceinline__ void load_block(KVFrag& f, const char* __restrict__ k
   for (int dt = 0; dt < 8; ++dt) f.v[dt] = *reinterpret_cast<const s16x4*>(vbase + dt * 512 + col * 32 + quad * 8);
 }
 
-__global__ __launch_bounds__(kWaves * 64) void decode_mfma_kernel(
+// One block's worth of work for one wavefront: scores, online softmax update, value
+// accumulation.  `tail` is the number of valid slots in the block (16 unless it is the
+// ragged last block of the sequence).
+__device__ __forceinline__ void process_block(KVFrag& f, const bf16x8 (&qf)[4], f32x4 (&acc)[8], float& m, float& l,
+                                              int tail, int quad, float scale_log2e) {
+  // S^T[token = 4*quad+i][head = col]
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[kk], qf[kk], s, 0, 0, 0);
+  s *= scale_log2e;
+  if (tail < 16) {
+    // ragged tail of the sequence: slots >= tail hold no token.  Their scores are excluded,
+    // and their V entries zeroed so that stale bits (possibly NaN) times a zero weight
+    // cannot reach the accumulator.
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (4 * quad + i >= tail) s[i] = -INFINITY;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (4 * quad + i >= tail) f.v[dt][i] = 0;
+  }
+  float bm = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  bm = fmaxf(bm, __shfl_xor(bm, 16));
+  bm = fmaxf(bm, __shfl_xor(bm, 32));
+  const float m_new = fmaxf(m, bm);  // finite: every block of the slice holds >= 1 token
+  const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+  f32x4 p;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - m_new);
+  l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));  // per-lane partial; quads are summed at the end
+  if (__any(m_new != m)) {
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
+  }
+  m = m_new;
+  const bf16x4 pb = __builtin_convertvector(p, bf16x4);
+  const s16x4 pbits = __builtin_bit_cast(s16x4, pb);
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(f.v[dt], pbits, acc[dt], 0, 0, 0);
+}
+
+// Exclusive prefix sums of the per-sequence block counts into LDS: pre[b] = blocks of
+// sequences 0..b-1, pre[B] = all.  Called by all 256 threads.
+__device__ __forceinline__ void scan_block_counts(int* pre, int* wsum, const int32_t* __restrict__ ctx_len, int B) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (B + kWaves * 64 - 1) / (kWaves * 64);
+  const int b0 = tid * per;
+  int local = 0;
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) local += (ctx_len[b0 + i] + 15) >> 4;
+  int x = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  if (lane == 63) wsum[wave] = x;
+  __syncthreads();
+  int run = x - local;
+  for (int w = 0; w < wave; ++w) run += wsum[w];
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) {
+      pre[b0 + i] = run;
+      run += (ctx_len[b0 + i] + 15) >> 4;
+    }
+  if (tid == 0) pre[B] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  __syncthreads();
+}
+
+// Chunk size in units: forced, or the equal share of the persistent grid's wavefronts.
+__device__ __forceinline__ long long chunk_units(long long U, int n_waves, int c_forced) {
+  if (c_forced > 0) return c_forced;
+  const long long c = (U + n_waves - 1) / n_waves;
+  return c < kMinSplitTokens / kBlockSize ? kMinSplitTokens / kBlockSize : c;
+}
+
+__global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
     const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
-    int ws_splits, int blocks_per_split, int Hq, int Hkv, int G, float scale_log2e) {
-  const int sp = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-  const int L = ctx_len[b];
-  const int nblk = (L + 15) >> 4;
-  const int n_split = (nblk + blocks_per_split - 1) / blocks_per_split;
-  if (sp >= n_split) return;
+    int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, int B, int Hq, int Hkv, int G, float scale_log2e) {
+  __shared__ int pre[kMaxBatch + 1];
+  __shared__ int wsum[kWaves];
+  scan_block_counts(pre, wsum, ctx_len, B);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, quad = lane >> 4;
-
-  // B operand of S^T: Q^T[d][head], heads beyond the group are zero columns
-  bf16x8 qf[4];
-  {
-    const uint16_t* qrow = q + ((size_t)b * Hq + (size_t)g * G + col) * 128;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[kk] = col < G ? *reinterpret_cast<const bf16x8*>(qrow + kk * 32 + quad * 8) : z;
-    }
+  const int n_waves = gridDim.x * kWaves;
+  const long long U = (long long)pre[B] * Hkv;
+  const long long C = chunk_units(U, n_waves, c_forced);
+  if (blockIdx.x == 0) {
+    // the merge kernel reads the numbering instead of recomputing it
+    for (int i = threadIdx.x; i <= B; i += kWaves * 64) ws_meta[2 + i] = pre[i];
+    if (threadIdx.x == 0) ws_meta[0] = (int)C;
   }
-
-  const int blk_begin = sp * blocks_per_split;
-  const int blk_end = min(nblk, blk_begin + blocks_per_split);
-  const int32_t* bt_row = block_table + (size_t)b * bt_stride;
-  const size_t head_off = (size_t)g * 4096;
+  const int gw = blockIdx.x * kWaves + wave;
+  long long u = (long long)gw * C;
+  const long long u_end = min(U, u + C);
   const size_t blk_stride = (size_t)Hkv * 4096;
 
-  f32x4 acc[8];
-#pragma unroll
-  for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, l = 0.f;
+  while (u < u_end) {
+    // locate the (sequence, head, block) of unit u: largest b with pre[b] <= u / Hkv
+    const int key = (int)(u / Hkv);
+    int lo = 0, hi = B;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pre[mid] <= key) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    const int nb = pre[b + 1] - pre[b];                    // blocks of this sequence
+    const long long seq_u0 = (long long)pre[b] * Hkv;
+    const int g = (int)((u - seq_u0) / nb);
+    const long long seg_u0 = seq_u0 + (long long)g * nb;   // first unit of (b, g)
+    const int blk0 = (int)(u - seg_u0);
+    const int n_piece = (int)(min(u_end, seg_u0 + nb) - u);
+    const int L = ctx_len[b];
 
-  int j = blk_begin + wave;
-  KVFrag cur;
-  if (j < blk_end) {
-    const size_t off = (size_t)__builtin_amdgcn_readfirstlane(bt_row[j]) * blk_stride + head_off;
-    load_block(cur, k_cache + off, v_cache + off, lane, col, quad);
-  }
-  while (j < blk_end) {
-    const int jn = j + kWaves;
-    KVFrag nxt;
-    if (jn < blk_end) {
-      const size_t off = (size_t)__builtin_amdgcn_readfirstlane(bt_row[jn]) * blk_stride + head_off;
-      load_block(nxt, k_cache + off, v_cache + off, lane, col, quad);
-    }
-
-    // S^T[token = 4*quad+i][head = col]
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    // B operand of S^T: Q^T[d][head], heads beyond the group are zero columns
+    bf16x8 qf[4];
+    {
+      const uint16_t* qrow = q + ((size_t)b * Hq + (size_t)g * G + col) * 128;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[kk], qf[kk], s, 0, 0, 0);
-    s *= scale_log2e;
-    if (j == nblk - 1) {
-      // ragged tail of the sequence: slots >= L % 16 hold no token.  Their scores are
-      // excluded, and their V entries zeroed so that stale bits (possibly NaN) times a
-      // zero weight cannot reach the accumulator.
-      const int tail = L - (j << 4);  // 1..16 valid slots
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (4 * quad + i >= tail) s[i] = -INFINITY;
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (4 * quad + i >= tail) cur.v[dt][i] = 0;
-    }
-    float bm = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-    bm = fmaxf(bm, __shfl_xor(bm, 16));
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
-    const float m_new = fmaxf(m, bm);  // finite: every block of the slice holds >= 1 token
-    const float alpha = exp2f(m - m_new);
-    f32x4 p;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) p[i] = exp2f(s[i] - m_new);
-    l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));  // per-lane partial; quads are summed at the end
-    if (__any(m_new != m)) {
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
-    }
-    m = m_new;
-    const bf16x4 pb = __builtin_convertvector(p, bf16x4);
-    const s16x4 pbits = __builtin_bit_cast(s16x4, pb);
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(cur.v[dt], pbits, acc[dt], 0, 0, 0);
-
-    cur = nxt;
-    j = jn;
-  }
-
-  // ---- merge the workgroup's wavefronts through LDS -------------------------------------
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
-  constexpr int kRow = 132;  // padded row of 128 floats
-  __shared__ float sm_acc[kWaves][kMaxGroup][kRow];
-  __shared__ float sm_m[kWaves][kMaxGroup];
-  __shared__ float sm_l[kWaves][kMaxGroup];
-  if (col < G) {
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-      *reinterpret_cast<f32x4*>(&sm_acc[wave][col][dt * 16 + 4 * quad]) = acc[dt];
-    if (quad == 0) {
-      sm_m[wave][col] = m;
-      sm_l[wave][col] = l;
-    }
-  }
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < G * 128; idx += kWaves * 64) {
-    const int hh = idx >> 7, d = idx & 127;
-    float M = sm_m[0][hh];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][hh]);
-    float lsum = 0.f, o = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float wgt = exp2f(sm_m[w][hh] - M);  // a wavefront without blocks has m = -inf -> weight 0
-      lsum += sm_l[w][hh] * wgt;
-      o += sm_acc[w][hh][d] * wgt;
-    }
-    const int h = g * G + hh;
-    if (n_split == 1) {
-      out[((size_t)b * Hq + h) * 128 + d] = float_to_bf16_bits(o / lsum);
-      if (lse && d == 0) lse[(size_t)b * Hq + h] = (M + log2f(lsum)) * kLn2;
-    } else {
-      const size_t slot = ((size_t)b * Hq + h) * ws_splits + sp;
-      ws_acc[slot * 128 + d] = o;
-      if (d == 0) {
-        ws_ml[slot * 2 + 0] = M;
-        ws_ml[slot * 2 + 1] = lsum;
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        qf[kk] = col < G ? *reinterpret_cast<const bf16x8*>(qrow + kk * 32 + quad * 8) : z;
       }
     }
+    const size_t head_off = (size_t)g * 4096;
+    const int32_t* bt_row = block_table + (size_t)b * bt_stride;
+
+    f32x4 acc[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    for (int base = 0; base < n_piece; base += 64) {
+      // physical ids of up to 64 consecutive logical blocks, lane i holding block base + i
+      const int n = min(64, n_piece - base);
+      int my_id = 0;
+      if (lane < n) my_id = bt_row[blk0 + base + lane];
+      // Register pipeline three blocks deep.  Loads are issued unconditionally with the
+      // index clamped to the last block (a harmless re-read that hits in cache), so the
+      // number of loads in flight is the same on every path and waits stay precise.
+      auto issue = [&](KVFrag& f, int i) {
+        const int ii = min(i, n - 1);
+        const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, ii) * blk_stride + head_off;
+        load_block(f, k_cache + off, v_cache + off, lane, col, quad);
+      };
+      auto tail_of = [&](int i) { return L - ((blk0 + base + i) << 4); };  // >= 16 except in the sequence's last block
+      KVFrag f0, f1, f2;
+      issue(f0, 0);
+      issue(f1, 1);
+      for (int i = 0; i < n; i += 3) {
+        issue(f2, i + 2);
+        process_block(f0, qf, acc, m, l, tail_of(i), quad, scale_log2e);
+        if (i + 1 >= n) break;
+        issue(f0, i + 3);
+        process_block(f1, qf, acc, m, l, tail_of(i + 1), quad, scale_log2e);
+        if (i + 2 >= n) break;
+        issue(f1, i + 4);
+        process_block(f2, qf, acc, m, l, tail_of(i + 2), quad, scale_log2e);
+      }
+    }
+
+    // ---- this piece's result: lanes (col = head, quad) hold o[d = 16 dt + 4 quad + i] --------
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (col < G) {
+      const int h = g * G + col;
+      if (n_piece == nb) {  // the whole (sequence, head): final
+        const float inv = 1.f / l;
+        uint16_t* orow = out + ((size_t)b * Hq + h) * 128;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          u32x2 w;
+          w[0] = (uint32_t)float_to_bf16_bits(acc[dt][0] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][1] * inv) << 16);
+          w[1] = (uint32_t)float_to_bf16_bits(acc[dt][2] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][3] * inv) << 16);
+          *reinterpret_cast<u32x2*>(orow + dt * 16 + 4 * quad) = w;
+        }
+        if (lse && quad == 0) lse[(size_t)b * Hq + h] = (m + log2f(l)) * kLn2;
+      } else {
+        const int split = gw - (int)(seg_u0 / C);
+        const size_t slot = ((size_t)b * Hq + h) * ws_splits + split;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
+        if (quad == 0) {
+          ws_ml[slot * 2 + 0] = m;
+          ws_ml[slot * 2 + 1] = l;
+        }
+      }
+    }
+    u += n_piece;
   }
 }
 
-hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t n_split_max,
-                              float* ws_acc, float* ws_ml, int32_t ws_splits, hipStream_t s) {
-  dim3 grid((unsigned)n_split_max, (unsigned)a.Hkv, (unsigned)a.B);
-  hipLaunchKernelGGL(decode_mfma_kernel, grid, dim3(kWaves * 64), 0, s, (const uint16_t*)a.q,
+// Merge of the partial softmax states of every (sequence, query head) that was cut:
+//   M = max_k m_k;  l = sum_k l_k 2^(m_k - M);  o = sum_k acc_k 2^(m_k - M) / l.
+// grid (Hq, B), 64 threads; lanes own pairs of head-vector elements.
+__global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __restrict__ ws_acc,
+                                                              const float* __restrict__ ws_ml,
+                                                              const int32_t* __restrict__ ws_meta, int ws_splits,
+                                                              uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                              int Hq, int Hkv, int G) {
+  const int h = blockIdx.x, b = blockIdx.y, g = h / G;
+  const long long C = ws_meta[0];
+  const int p0 = ws_meta[2 + b], nb = ws_meta[2 + b + 1] - p0;
+  const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nb;
+  const int n_split = (int)((seg_u0 + nb - 1) / C - seg_u0 / C) + 1;
+  if (n_split <= 1) return;  // written in final form by the decode kernel
+  const size_t base = ((size_t)b * Hq + h) * ws_splits;
+  const int lane = threadIdx.x;
+  float M = -INFINITY;
+  for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[(base + k) * 2]);
+  float lsum = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int k = 0; k < n_split; ++k) {
+    const float w = exp2f(ws_ml[(base + k) * 2] - M);
+    lsum += ws_ml[(base + k) * 2 + 1] * w;
+    const float2 a = *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane);
+    o0 += a.x * w;
+    o1 += a.y * w;
+  }
+  const float inv = 1.f / lsum;
+  const uint32_t w = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
+  *reinterpret_cast<uint32_t*>(out + ((size_t)b * Hq + h) * 128 + 2 * lane) = w;
+  if (lse && lane == 0) lse[(size_t)b * Hq + h] = (M + log2f(lsum)) * kLn2;
+}
+
+hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
+                              int32_t num_cu, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
+                              hipStream_t s) {
+  const int G = a.Hq / a.Hkv;
+  int n_wg = 2 * num_cu;  // persistent: two workgroups per CU (register budget of the pipeline)
+  int c_forced = 0;
+  if (split_tokens > 0) {
+    // forced chunk size: the grid must cover the largest possible number of units
+    c_forced = split_tokens / kBlockSize;
+    const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize);
+    const long long waves = (u_max + c_forced - 1) / c_forced;
+    n_wg = (int)((waves + kWaves - 1) / kWaves);
+  }
+  hipLaunchKernelGGL(decode_mfma_kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q,
                      (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
-                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_splits, split_tokens / kBlockSize, a.Hq, a.Hkv,
-                     a.Hq / a.Hkv, a.scale_log2e);
+                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, a.B, a.Hq, a.Hkv, G,
+                     a.scale_log2e);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
+                                    const int32_t* ws_meta, int32_t ws_splits, hipStream_t s) {
+  hipLaunchKernelGGL(decode_flat_merge_kernel, dim3((unsigned)a.Hq, (unsigned)a.B), dim3(64), 0, s, ws_acc, ws_ml,
+                     ws_meta, ws_splits, (uint16_t*)a.out, a.lse, a.Hq, a.Hkv, a.Hq / a.Hkv);
   return hipGetLastError();
 }
 

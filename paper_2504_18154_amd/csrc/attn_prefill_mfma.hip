@@ -8,14 +8,17 @@
 // same loop).
 //
 // Work decomposition: one workgroup (4 wavefronts) = 128 query rows of one query head;
-// each wavefront owns 32 rows.  Workgroup ids are laid out so that consecutive ids differ
-// first in the K/V head (ids are dealt round-robin to the 8 XCDs, so with 8 K/V heads
-// each XCD's L2 holds one head's K/V), then in the query head of the group, then in the
-// query tile (heaviest, i.e. last, tile first), then in the sequence.
+// each wavefront owns 32 rows; two workgroups share a CU so that one's softmax (VALU)
+// runs under the other's matrix work.  Workgroup ids are laid out so that consecutive ids
+// differ first in the K/V head (ids are dealt round-robin to the 8 XCDs, so with 8 K/V
+// heads each XCD's L2 holds one head's K/V), then in the query head of the group, then in
+// the query tile (heaviest, i.e. last, tile first), then in the sequence.
 //
-// Per 64-key step: the four 16-token cache blocks of K and of V are copied (global ->
-// registers -> LDS, double buffered, one barrier per step) in 16-byte units.  The cache
-// layouts were chosen so that no transposition is needed anywhere:
+// Per 64-key step the four 16-token cache blocks of K and of V go straight from global
+// memory into LDS (global_load ... lds, 16 bytes per lane, double buffered, one barrier per
+// step); each lane picks the source address of the 16-byte unit that belongs at its LDS
+// position, so the copy also performs the re-tiling.  The cache layouts were chosen so
+// that no transposition is needed anywhere:
 //   K block  [16 units][16 tokens][8 elems]  ->  LDS [unit][64 keys][16 B]:  A operand of
 //            S^T = K Q^T   (v_mfma_f32_32x32x16_bf16, rows = keys, cols = query rows)
 //   V block  [128 d][16 tokens]              ->  LDS [8-key octet][128 d][16 B]:  A operand
@@ -23,8 +26,15 @@
 // The rows of each S^T tile are assigned to keys with bits 2 and 3 swapped so that the
 // accumulator registers a lane holds (rows 8*(i/4) + 4*half + i%4) are 8 consecutive keys,
 // which is exactly the B-operand fragment of the second product: P stays in registers.
-// Softmax is the online form per query row (= per accumulator column: in-lane over 32
-// values, one cross-half shuffle), in the exp2 domain with the scale folded into one FMA.
+//
+// Softmax is the online form per query row (= per accumulator column: in-lane over the
+// lane's values, one v_permlane32_swap across the two halves), in the exp2 domain with the
+// scale folded into one FMA.  The running maximum used in the exponent is only raised when
+// a tile's maximum exceeds it by more than 2^8 (the accumulator and the row sum are then
+// rescaled); weights can therefore reach 2^8, which bf16 and fp32 hold without loss of
+// relative precision, and the rescale multiplications almost vanish from the loop.  The
+// row sum is accumulated from the bf16-rounded weights with v_dot2_f32_bf16, so numerator
+// and denominator see the same rounding.
 //
 // Lane layout relied upon for 32x32x16 (lane = 32*half + col):
 //   A[row = col][k = 8*half .. +7],  B[k = 8*half .. +7][col],
@@ -36,56 +46,117 @@ namespace eco {
 constexpr int kTQ = 128;                       // query rows per workgroup
 constexpr int kTK = 64;                        // keys per step
 constexpr int kKTileBytes = 16 * kTK * 16;     // [16 units][64 keys][16 B]
-constexpr int kVOctStride = 128 * 16 + 64;     // one 8-key octet: [128 d][16 B] + bank-spreading pad
+constexpr int kVOctStride = 128 * 16 + 64;     // one 8-key octet: [128 d][16 B] + pad
 constexpr int kVTileBytes = 8 * kVOctStride;
 constexpr int kBufBytes = kKTileBytes + kVTileBytes;
+constexpr float kTau = 8.f;                    // lazy-rescale threshold, log2 units
 
-struct Stage {
-  u32x4 k[4];
-  u32x4 v[4];
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Physical block ids a lane needs to stage key tile `it`: idk for its K quarter (block
+// lane/16 of the tile), idv for the V block its wavefront copies.  Blocks past the
+// sequence's last one are replaced by the last one (their keys are beyond every causal
+// bound; fix_tail() zeroes their values).
+struct TileIds {
+  int idk, idv;
 };
+__device__ __forceinline__ TileIds load_ids(const int32_t* __restrict__ bt_row, int it, int nblk_total, int wave,
+                                            int lane) {
+  const int last = nblk_total - 1;
+  TileIds t;
+  t.idk = bt_row[min(it * 4 + (lane >> 4), last)];
+  t.idv = bt_row[min(it * 4 + wave, last)];
+  return t;
+}
 
-__device__ __forceinline__ void load_tile(Stage& st, const char* __restrict__ k_cache,
-                                          const char* __restrict__ v_cache, const int32_t* __restrict__ bt_row,
-                                          int it, int nblk_total, int L_total, size_t head_off, size_t blk_stride,
-                                          int tid) {
+// Issue the global->LDS copies of one key tile (64 keys).
+__device__ __forceinline__ void stage_tile(char* buf, const char* __restrict__ k_cache,
+                                           const char* __restrict__ v_cache, TileIds ids, size_t head_off,
+                                           size_t blk_stride, int wave, int lane) {
+  // K: this wavefront copies units u = 4*wave .. 4*wave+3 of all four blocks; a 1 KiB LDS
+  // chunk is one unit of 64 keys, so lane l fetches (block l/16, token l%16)
+  const char* ksrc = k_cache + (size_t)ids.idk * blk_stride + head_off + (size_t)(lane & 15) * 16;
+  // V: this wavefront copies block `wave`: octets 2*wave, 2*wave+1; a 1 KiB LDS chunk is 64
+  // consecutive d of one octet, so lane l fetches unit (d = 64 hd + l, half)
+  const char* vsrc = v_cache + (size_t)ids.idv * blk_stride + head_off + (size_t)lane * 32;
 #pragma unroll
-  for (int jb = 0; jb < 4; ++jb) {
-    const int j = it * 4 + jb;
-    if (j < nblk_total) {
-      const size_t off = (size_t)__builtin_amdgcn_readfirstlane(bt_row[j]) * blk_stride + head_off + (size_t)tid * 16;
-      st.k[jb] = *reinterpret_cast<const u32x4*>(k_cache + off);
-      u32x4 v = *reinterpret_cast<const u32x4*>(v_cache + off);
-      const int tail = L_total - (j << 4);  // valid slots in this block
-      if (tail < 16) {
-        // stale slots of the sequence's last block: zero them so that 0 * garbage cannot
-        // reach the accumulator.  This thread's unit holds slots 8*(tid&1) .. +7.
-        const int s0 = (tid & 1) * 8;
+  for (int i = 0; i < 4; ++i) {
+    const int u = 4 * wave + i;
+    __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + u * 256), (lptr_t)(buf + u * 1024), 16, 0, 0);
+  }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int lo_slot = s0 + 2 * e;
-          uint32_t w = v[e];
-          if (lo_slot >= tail) w &= 0xffff0000u;
-          if (lo_slot + 1 >= tail) w &= 0x0000ffffu;
-          v[e] = w;
-        }
-      }
-      st.v[jb] = v;
-    } else {
-      st.k[jb] = u32x4{0, 0, 0, 0};
-      st.v[jb] = u32x4{0, 0, 0, 0};
-    }
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int hd = 0; hd < 2; ++hd)
+      __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + hd * 2048 + hf * 16),
+                                       (lptr_t)(buf + kKTileBytes + (2 * wave + hf) * kVOctStride + hd * 1024), 16,
+                                       0, 0);
+}
+
+// Zero the V entries of keys >= first_bad of the tile in `buf` (slots past the end of the
+// sequence may hold anything, and 0 * NaN must not reach the accumulator).
+__device__ __forceinline__ void fix_tail(char* buf, int first_bad, int tid) {
+  const int n = (kTK - first_bad) * 128;
+  for (int idx = tid; idx < n; idx += 256) {
+    const int key = first_bad + (idx >> 7), d = idx & 127;
+    *reinterpret_cast<uint16_t*>(buf + kKTileBytes + (key >> 3) * kVOctStride + d * 16 + (key & 7) * 2) = 0;
   }
 }
 
-__device__ __forceinline__ void store_tile(const Stage& st, char* buf, int tid) {
+struct RowState {
+  float m;  // maximum used in the exponent (raw score units); -inf before the first key
+  float l;  // this lane's share of the row sum
+};
+
+// Online-softmax update for one 32-key S^T tile (16 accumulator values per lane): masks,
+// raises the running maximum if needed (rescaling o and l), turns scores into bf16
+// weights (two B-operand fragments of 8 keys each) and adds them to the row sum.
+__device__ __forceinline__ void softmax_tile(f32x16& s, bf16x8 (&pf)[2], RowState& st, f32x16 (&o)[4], int key_base,
+                                             int half, int pos, bool masked, float c) {
+  if (masked) {
 #pragma unroll
-  for (int jb = 0; jb < 4; ++jb) {
-    // K: thread's unit is (unit c = tid/16, token = tid%16) of block jb
-    *reinterpret_cast<u32x4*>(buf + (((tid >> 4) * kTK) + jb * 16 + (tid & 15)) * 16) = st.k[jb];
-    // V: thread's unit is (d = tid/2, half = tid%2) -> octet 2*jb + half
-    *reinterpret_cast<u32x4*>(buf + kKTileBytes + (2 * jb + (tid & 1)) * kVOctStride + (tid >> 1) * 16) = st.v[jb];
+    for (int i = 0; i < 16; ++i) {
+      const int key = key_base + (i >> 3) * 16 + half * 8 + (i & 7);
+      if (key > pos) s[i] = -INFINITY;
+    }
   }
+  float bm = fmaxf(s[0], s[1]);
+#pragma unroll
+  for (int i = 2; i < 16; i += 2) bm = fmaxf(bm, fmaxf(s[i], s[i + 1]));
+  {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(bm), __float_as_uint(bm), false, false);
+    bm = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  }
+  if (__any((bm - st.m) * c > kTau)) {
+    const float m_new = fmaxf(st.m, bm);
+    const float alpha = __builtin_amdgcn_exp2f((st.m - m_new) * c);
+    st.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
+    st.m = m_new;
+  }
+  const float mc = st.m * c;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  float l0 = st.l, l1 = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; i += 4) {
+    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 0], c, -mc));
+    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 1], c, -mc));
+    const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 2], c, -mc));
+    const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 3], c, -mc));
+    const bf16x2 a = {(__bf16)p0, (__bf16)p1};
+    const bf16x2 b = {(__bf16)p2, (__bf16)p3};
+    l0 = __builtin_amdgcn_fdot2_f32_bf16(a, ones, l0, false);
+    l1 = __builtin_amdgcn_fdot2_f32_bf16(b, ones, l1, false);
+    const int f = i >> 3, e = i & 7;
+    pf[f][e + 0] = a[0];
+    pf[f][e + 1] = a[1];
+    pf[f][e + 2] = b[0];
+    pf[f][e + 3] = b[1];
+  }
+  st.l = l0 + l1;
 }
 
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
@@ -106,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   const int qt = n_qt - 1 - qt_rev;
   if (qt < 0) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
   const int h = g * G + hg;
   const int cb = ctx_before[b];
@@ -120,6 +191,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   const int pos = cb + row;                            // absolute position = causal bound
   const int w_pmin = cb + q0 + wave * 32;              // smallest / largest bound in this wavefront
   const int w_pmax = cb + min(S - 1, q0 + wave * 32 + 31);
+
+  const int32_t* bt_row = block_table + (size_t)b * bt_stride;
+  const size_t head_off = (size_t)g * 4096;
+  const size_t blk_stride = (size_t)Hkv * 4096;
+
+  stage_tile(smem, k_cache, v_cache, load_ids(bt_row, 0, nblk_total, wave, lane), head_off, blk_stride, wave, lane);
+  TileIds next_ids = load_ids(bt_row, 1, nblk_total, wave, lane);  // ids run one tile ahead of the copies
 
   // B operand of S^T: Q^T[d][row]; step t covers d = 16 t .. 16 t + 15
   bf16x8 qf[8];
@@ -137,94 +215,86 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-  float m = -INFINITY, l = 0.f;  // running max of raw scores (unscaled), per-lane partial sum
+  RowState st{-INFINITY, 0.f};
 
-  const int32_t* bt_row = block_table + (size_t)b * bt_stride;
-  const size_t head_off = (size_t)g * 4096;
-  const size_t blk_stride = (size_t)Hkv * 4096;
   // A-operand row -> key inside a 32-key tile: swap bits 2 and 3
   const int krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
+  const int a_k_off = (half * kTK + krow) * 16;            // + (2 t * 64 + 32 sub) * 16
+  const int a_v_off = half * kVOctStride + col * 16;       // + 2 u * stride + 32 dt * 16
 
-  Stage st;
-  load_tile(st, k_cache, v_cache, bt_row, 0, nblk_total, L_total, head_off, blk_stride, tid);
-  store_tile(st, smem, tid);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-
-  for (int it = 0; it < n_tiles; ++it) {
-    const char* buf = smem + (it & 1) * kBufBytes;
-    if (it + 1 < n_tiles)
-      load_tile(st, k_cache, v_cache, bt_row, it + 1, nblk_total, L_total, head_off, blk_stride, tid);
-
-    const int k0 = it * kTK;
-    if (k0 <= w_pmax) {  // uniform per wavefront: tiles wholly above the diagonal are skipped
-      f32x16 s[2];
-#pragma unroll
-      for (int sti = 0; sti < 2; ++sti) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[sti][i] = 0.f;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const bf16x8 a =
-              *reinterpret_cast<const bf16x8*>(buf + (((2 * t + half) * kTK) + sti * 32 + krow) * 16);
-          s[sti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], s[sti], 0, 0, 0);
-        }
-      }
-      if (k0 + kTK - 1 > w_pmin) {  // diagonal tile: apply the causal bound
-#pragma unroll
-        for (int sti = 0; sti < 2; ++sti)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = k0 + sti * 32 + (i >> 3) * 16 + half * 8 + (i & 7);
-            if (key > pos) s[sti][i] = -INFINITY;
-          }
-      }
-      float bm = s[0][0];
-#pragma unroll
-      for (int sti = 0; sti < 2; ++sti)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) bm = fmaxf(bm, s[sti][i]);
-      bm = fmaxf(bm, __shfl_xor(bm, 32));
-      const float m_new = fmaxf(m, bm);
-      const float mc = m_new * scale_log2e;
-      const float alpha = exp2f(m * scale_log2e - mc);
-      float psum = 0.f;
-#pragma unroll
-      for (int sti = 0; sti < 2; ++sti)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = exp2f(__builtin_fmaf(s[sti][i], scale_log2e, -mc));
-          s[sti][i] = p;
-          psum += p;
-        }
-      l = l * alpha + psum;
-      if (__any(m_new != m)) {
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
-      }
-      m = m_new;
-      // B operand of O^T: P^T[key][row]; step u covers keys 16 u .. 16 u + 15 of the tile
-      bf16x8 pf[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[u][e] = (__bf16)s[u >> 1][(u & 1) * 8 + e];
-      const char* vbuf = buf + kKTileBytes;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(vbuf + (2 * u + half) * kVOctStride + (dt * 32 + col) * 16);
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[u], o[dt], 0, 0, 0);
-        }
-    }
-
-    if (it + 1 < n_tiles) store_tile(st, smem + ((it + 1) & 1) * kBufBytes, tid);
+  if (kTK > L_total) {  // the first tile already runs past the end of the sequence
+    fix_tail(smem, L_total, tid);
     __syncthreads();
   }
 
-  l += __shfl_xor(l, 32);
+  for (int it = 0; it < n_tiles; ++it) {
+    const char* buf = smem + (it & 1) * kBufBytes;
+    char* nbuf = smem + ((it + 1) & 1) * kBufBytes;
+    if (it + 1 < n_tiles) {
+      stage_tile(nbuf, k_cache, v_cache, next_ids, head_off, blk_stride, wave, lane);
+      next_ids = load_ids(bt_row, it + 2, nblk_total, wave, lane);
+    }
+
+    const int k0 = it * kTK;
+    if (k0 <= w_pmax) {  // uniform per wavefront: tiles wholly above the diagonal are skipped
+      const bool masked = k0 + kTK - 1 > w_pmin;
+      const bool second = k0 + 32 <= w_pmax;  // the second 32 keys are not wholly above the diagonal
+      const char* kb = buf + a_k_off;
+      const char* vb = buf + kKTileBytes + a_v_off;
+      f32x16 s0, s1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+      bf16x8 pf0[2], pf1[2];
+      // keys 0..31: scores
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + (2 * t * kTK) * 16);
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], s0, 0, 0, 0);
+      }
+      if (second) {
+        // keys 32..63: scores, issued before the first half's softmax so the two overlap
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + (2 * t * kTK + 32) * 16);
+          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], s1, 0, 0, 0);
+        }
+      }
+      softmax_tile(s0, pf0, st, o, k0, half, pos, masked, scale_log2e);
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(vb + 2 * u * kVOctStride + dt * 32 * 16);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf0[u], o[dt], 0, 0, 0);
+        }
+      if (second) {
+        softmax_tile(s1, pf1, st, o, k0 + 32, half, pos, masked, scale_log2e);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(vb + (2 * u + 4) * kVOctStride + dt * 32 * 16);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf1[u], o[dt], 0, 0, 0);
+          }
+      }
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + 1 < n_tiles && (it + 2) * kTK > L_total) {  // the next tile runs past the end of the sequence
+      fix_tail(nbuf, L_total - (it + 1) * kTK, tid);
+      __syncthreads();
+    }
+  }
+
+  {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(st.l), __float_as_uint(st.l), false, false);
+    st.l = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
   if (row_valid) {
-    const float inv = 1.f / l;
+    const float inv = 1.f / st.l;
     uint16_t* orow = out + ((size_t)(tok0 + row) * Hq + h) * 128;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
@@ -238,7 +308,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
                ((uint32_t)float_to_bf16_bits(o[dt][4 * i4 + 3] * inv) << 16);
         *reinterpret_cast<u32x2*>(orow + dt * 32 + i4 * 8 + half * 4) = w;
       }
-    if (lse && half == 0) lse[(size_t)(tok0 + row) * Hq + h] = (m * scale_log2e + log2f(l)) * kLn2;
+    if (lse && half == 0) lse[(size_t)(tok0 + row) * Hq + h] = (st.m * scale_log2e + log2f(st.l)) * kLn2;
   }
 }
 

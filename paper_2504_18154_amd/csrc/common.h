@@ -13,6 +13,8 @@ namespace eco {
 constexpr int kBlockSize = 16;        // tokens per cache block (the only supported value)
 constexpr int kMaxGroup = 16;         // largest supported Hq / Hkv
 constexpr int kMinSplitTokens = 64;   // smallest decode split
+constexpr int kMaxSplitTokens = 4096; // largest forced decode split
+constexpr int kMaxBatch = 4096;       // largest max_batch a context accepts (batch prefix sums live in LDS)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -36,6 +38,7 @@ struct ecoserve_ctx {
   // split-context workspace: unnormalised partial outputs and (max, sum) pairs
   float* ws_acc;               // [max_batch][Hq][ws_splits][D]
   float* ws_ml;                // [max_batch][Hq][ws_splits][2]
+  int32_t* ws_meta;            // [max_batch + 3]: chunk size and batch prefix sums of the last decode launch
   int32_t ws_splits;
   size_t ws_bytes;
   // profiling
@@ -76,8 +79,12 @@ hipError_t launch_decode_merge(const AttnArgs& a, const int32_t* ctx_len, int32_
                                const float* ws_ml, int32_t ws_splits, hipStream_t s);
 
 // attn_decode_mfma.hip: bf16, D = 128
-hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t n_split_max,
-                              float* ws_acc, float* ws_ml, int32_t ws_splits, hipStream_t s);
+// (split_tokens 0 = equal share per wavefront of the persistent grid; > 0 forces the chunk size)
+hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
+                              int32_t num_cu, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
+                              hipStream_t s);
+hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
+                                    const int32_t* ws_meta, int32_t ws_splits, hipStream_t s);
 
 // attn_prefill_mfma.hip: bf16, D = 128
 hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,

@@ -14,7 +14,10 @@ from paper_2504_18154_amd import workloads as wl
 # bar.  fp32: derived from fp32 accumulation over a few hundred keys plus exp2 error,
 # with two orders of magnitude of headroom.
 TOL = {"bf16": (1e-2, 1e-3), "f32": (1e-4, 1e-5)}
-LSE_TOL = {"bf16": 1e-3, "f32": 1e-4}
+# log-sum-exp (natural log).  The prefill kernel sums the bf16-rounded weights (the same
+# values the second product consumes), so the row sum carries a relative error of at most
+# half a bf16 spacing, 2^-9 = 1.95e-3, which is also the bound on the error of its log.
+LSE_TOL = {"bf16": 2.5e-3, "f32": 1e-4}
 
 
 def say(msg: str):
