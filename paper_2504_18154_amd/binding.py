@@ -40,11 +40,11 @@ class EcoserveError(RuntimeError):
         self.status = status
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_18154_amd.build` "
+def _load(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2504_18154_amd.build` "
                           "(there is no fallback path)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
     lib.ecoserve_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.POINTER(Layout), i32, i32]
     lib.ecoserve_destroy.argtypes = [vp]
