@@ -8,52 +8,121 @@
 // Source rows are [T][Hkv][D]; destination is the library's block layout
 //   K: [blk][Hkv][D/x][16 slots][x]   (x = elements per 16 bytes)
 //   V: [blk][Hkv][D][16 slots]
-// One thread moves one 16-byte unit of K (a single 16-byte store) and the same x
-// elements of V (x element stores, 16 slots apart).
+// One workgroup fills one (destination block, K/V head): up to 16 token rows in, one
+// contiguous K piece and one contiguous V piece out (4 KiB each for bf16, D = 128).
+// K units keep their 16 bytes and only change place, so they are copied directly with the
+// writes running along the destination.  V needs a transposition (16 slots of one element
+// become contiguous): the token rows are staged in LDS with coalesced reads and written
+// back as 16-byte units along the destination.  Blocks that are only partly addressed
+// (the first block of an append that continues a sequence, the last block) write only the
+// addressed slots, element by element where a 16-byte unit is not completely new.
+//
+// The destination blocks of the whole batch are numbered sequence after sequence; the grid
+// covers an upper bound on their number that the host can compute (T/16 + 2 per sequence),
+// and every workgroup finds its (sequence, block) from a prefix sum over the batch.
 #include "common.h"
 
 namespace eco {
 
-// Index of the sequence that owns packed token t: largest b with cu_q[b] <= t.
-__device__ __forceinline__ int find_sequence(const int32_t* __restrict__ cu_q, int B, int t) {
-  int lo = 0, hi = B;  // invariant: cu_q[lo] <= t < cu_q[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (cu_q[mid] <= t) lo = mid; else hi = mid;
+constexpr int kAppendThreads = 256;
+
+// Exclusive prefix sums over the batch of the number of cache blocks each sequence's new
+// tokens touch: pre[b] = blocks of sequences 0..b-1, pre[B] = all.  Called by all threads.
+__device__ __forceinline__ void scan_touched_blocks(int* pre, int* wsum, const int32_t* __restrict__ cu_q,
+                                                    const int32_t* __restrict__ ctx_before, int B) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (B + kAppendThreads - 1) / kAppendThreads;
+  const int b0 = tid * per;
+  auto touched = [&](int b) {
+    const int S = cu_q[b + 1] - cu_q[b], cb = ctx_before[b];
+    return S > 0 ? ((cb + S - 1) >> 4) - (cb >> 4) + 1 : 0;
+  };
+  int local = 0;
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) local += touched(b0 + i);
+  int x = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
   }
-  return lo;
+  if (lane == 63) wsum[wave] = x;
+  __syncthreads();
+  int run = x - local;
+  for (int w = 0; w < wave; ++w) run += wsum[w];
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) {
+      pre[b0 + i] = run;
+      run += touched(b0 + i);
+    }
+  if (tid == 0) pre[B] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  __syncthreads();
 }
 
 template <typename E>
-__global__ __launch_bounds__(256) void kv_append_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
-                                                        const E* __restrict__ k_new, const E* __restrict__ v_new,
-                                                        const int32_t* __restrict__ cu_q,
-                                                        const int32_t* __restrict__ ctx_before,
-                                                        const int32_t* __restrict__ block_table, int bt_stride,
-                                                        int B, int T, int Hkv, int D) {
+__global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
+                                                                    const E* __restrict__ k_new,
+                                                                    const E* __restrict__ v_new,
+                                                                    const int32_t* __restrict__ cu_q,
+                                                                    const int32_t* __restrict__ ctx_before,
+                                                                    const int32_t* __restrict__ block_table,
+                                                                    int bt_stride, int B, int Hkv, int D) {
   constexpr int X = Elem<E>::X;
-  const int units_per_row = D / X;
-  const int64_t total = (int64_t)T * Hkv * units_per_row;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int c = (int)(idx % units_per_row);
-  const int g = (int)((idx / units_per_row) % Hkv);
-  const int t = (int)(idx / ((int64_t)units_per_row * Hkv));
-  const int b = find_sequence(cu_q, B, t);
-  const int p = ctx_before[b] + (t - cu_q[b]);
-  const int64_t blk = block_table[(size_t)b * bt_stride + (p >> 4)];
-  const int slot = p & 15;
-
-  const size_t src = ((size_t)t * Hkv + g) * D + (size_t)c * X;
   typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-  const u4 kval = *reinterpret_cast<const u4*>(k_new + src);
-  *reinterpret_cast<u4*>(k_cache + k_index<X>(blk, g, slot, c * X, Hkv, D)) = kval;
+  __shared__ int pre[kMaxBatch + 1];
+  __shared__ int wsum[kAppendThreads / 64];
+  __shared__ __attribute__((aligned(16))) E vt[16][256 + X];  // staged V rows (D <= 256), padded
+  scan_touched_blocks(pre, wsum, cu_q, ctx_before, B);
 
-  const u4 vraw = *reinterpret_cast<const u4*>(v_new + src);
-  const E* ve = reinterpret_cast<const E*>(&vraw);
-  E* vdst = v_cache + v_index(blk, g, slot, c * X, Hkv, D);
+  const int unit = blockIdx.x;  // destination block number within the batch
+  if (unit >= pre[B]) return;
+  int lo_b = 0, hi_b = B;
+  while (hi_b - lo_b > 1) {
+    const int mid = (lo_b + hi_b) >> 1;
+    if (pre[mid] <= unit) lo_b = mid; else hi_b = mid;
+  }
+  const int b = lo_b, g = blockIdx.y, tid = threadIdx.x;
+  const int tok0 = cu_q[b], S = cu_q[b + 1] - tok0, cb = ctx_before[b];
+  const int j = (cb >> 4) + (unit - pre[b]);          // logical block of the sequence
+  const int lo = max(0, cb - (j << 4));               // addressed slots [lo, hi) of this block
+  const int hi = min(16, cb + S - (j << 4));
+  const int t_slot0 = tok0 + (j << 4) - cb;           // packed token index of slot 0 (may be < tok0)
+  const int64_t blk = block_table[(size_t)b * bt_stride + j];
+  const int upr = D / X;                              // 16-byte units per head row
+
+  // K: unit (c, slot) -> destination [c][slot][X]; threads run along the destination
+  E* kdst = k_cache + ((size_t)blk * Hkv + g) * 16 * D;
+  for (int u = tid; u < 16 * upr; u += kAppendThreads) {
+    const int slot = u & 15, c = u >> 4;
+    if (slot >= lo && slot < hi) {
+      const u4 val = *reinterpret_cast<const u4*>(k_new + ((size_t)(t_slot0 + slot) * Hkv + g) * D + c * X);
+      *reinterpret_cast<u4*>(kdst + (size_t)u * X) = val;
+    }
+  }
+  // V: stage rows (threads run along the source rows) ...
+  for (int u = tid; u < 16 * upr; u += kAppendThreads) {
+    const int slot = u / upr, c = u % upr;
+    if (slot >= lo && slot < hi)
+      *reinterpret_cast<u4*>(&vt[slot][c * X]) =
+          *reinterpret_cast<const u4*>(v_new + ((size_t)(t_slot0 + slot) * Hkv + g) * D + c * X);
+  }
+  __syncthreads();
+  // ... and write [d][16 slots] in 16-byte units of X slots (threads run along the destination)
+  E* vdst = v_cache + ((size_t)blk * Hkv + g) * D * 16;
+  constexpr int kGroups = 16 / X;  // 16-byte units per element row
+  for (int u = tid; u < D * kGroups; u += kAppendThreads) {
+    const int d = u / kGroups, s0 = (u % kGroups) * X;
+    if (s0 >= lo && s0 + X <= hi) {
+      E tmp[X];
 #pragma unroll
-  for (int e = 0; e < X; ++e) vdst[(size_t)e * kBlockSize] = ve[e];
+      for (int e = 0; e < X; ++e) tmp[e] = vt[s0 + e][d];
+      *reinterpret_cast<u4*>(vdst + (size_t)d * 16 + s0) = *reinterpret_cast<const u4*>(tmp);
+    } else {
+#pragma unroll
+      for (int e = 0; e < X; ++e)
+        if (s0 + e >= lo && s0 + e < hi) vdst[(size_t)d * 16 + s0 + e] = vt[s0 + e][d];
+    }
+  }
 }
 
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
@@ -61,16 +130,16 @@ hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cach
                             const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
                             int32_t /*max_new_len*/, hipStream_t s) {
   const ecoserve_layout& L = ctx->lay;
-  const int X = L.dtype == ECOSERVE_BF16 ? 8 : 4;
-  const int64_t total = (int64_t)T * L.num_kv_heads * (L.head_dim / X);
-  const unsigned grid = (unsigned)((total + 255) / 256);
+  // a sequence with S new tokens touches at most S/16 + 2 blocks (ragged at both ends), and none if S == 0
+  const int64_t max_units = (int64_t)T / 16 + 2 * (int64_t)(B < T ? B : T);
+  const dim3 grid((unsigned)max_units, (unsigned)L.num_kv_heads);
   if (L.dtype == ECOSERVE_BF16) {
-    hipLaunchKernelGGL(kv_append_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (uint16_t*)k_cache,
+    hipLaunchKernelGGL(kv_append_kernel<uint16_t>, grid, dim3(kAppendThreads), 0, s, (uint16_t*)k_cache,
                        (uint16_t*)v_cache, (const uint16_t*)k_new, (const uint16_t*)v_new, cu_q, ctx_before,
-                       block_table, bt_stride, B, T, L.num_kv_heads, L.head_dim);
+                       block_table, bt_stride, B, L.num_kv_heads, L.head_dim);
   } else {
-    hipLaunchKernelGGL(kv_append_kernel<float>, dim3(grid), dim3(256), 0, s, (float*)k_cache, (float*)v_cache,
-                       (const float*)k_new, (const float*)v_new, cu_q, ctx_before, block_table, bt_stride, B, T,
+    hipLaunchKernelGGL(kv_append_kernel<float>, grid, dim3(kAppendThreads), 0, s, (float*)k_cache, (float*)v_cache,
+                       (const float*)k_new, (const float*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
                        L.num_kv_heads, L.head_dim);
   }
   return hipGetLastError();
