@@ -12,7 +12,8 @@
 // runs under the other's matrix work.  Workgroup ids are laid out so that consecutive ids
 // differ first in the K/V head (ids are dealt round-robin to the 8 XCDs, so with 8 K/V
 // heads each XCD's L2 holds one head's K/V), then in the query head of the group, then in
-// the query tile (heaviest, i.e. last, tile first), then in the sequence.
+// the query tile (heaviest, i.e. last, tile first), then in the sequence; only tiles that
+// exist are launched (plus a few surplus workgroups that exit at once).
 //
 // Per 64-key step the four 16-token cache blocks of K and of V go straight from global
 // memory into LDS (global_load ... lds, 16 bytes per lane, double buffered, one barrier per
@@ -156,21 +157,59 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ ctx_before,
     const int32_t* __restrict__ block_table, int bt_stride, uint16_t* __restrict__ out, float* __restrict__ lse,
-    int B, int Hq, int Hkv, int G, int n_qt_max, float scale_log2e) {
+    int B, int Hq, int Hkv, int G, float scale_log2e) {
   __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes];
+  static_assert((kMaxBatch + 1 + 4) * 4 <= 2 * kKTileBytes + 2 * kVTileBytes, "batch prefix sums must fit in the tile buffers");
   char* const kbufs = smem;
   char* const vbufs = smem + 2 * kKTileBytes;
 
+  // Query tiles of the whole batch are numbered sequence after sequence, last (heaviest)
+  // tile of a sequence first.  The grid covers an upper bound on their number that the host
+  // can compute; every workgroup finds its (sequence, tile) from a prefix sum over the batch,
+  // held in the LDS that the K/V buffers take over afterwards.
   int wg = blockIdx.x;
   const int g = wg % Hkv;  wg /= Hkv;
   const int hg = wg % G;   wg /= G;
-  const int qt_rev = wg % n_qt_max;
-  const int b = wg / n_qt_max;
+  const int tile_id = wg;
+  int b, qt;
+  {
+    int* pre = reinterpret_cast<int*>(smem);            // [B + 1]
+    int* wsum = pre + kMaxBatch + 1;                    // [4]
+    const int t = threadIdx.x, ln = t & 63, wv = t >> 6;
+    const int per = (B + 255) / 256, b0 = t * per;
+    int local = 0;
+    for (int i = 0; i < per; ++i)
+      if (b0 + i < B) local += (cu_q[b0 + i + 1] - cu_q[b0 + i] + kTQ - 1) / kTQ;
+    int x = local;
+#pragma unroll
+    for (int o2 = 1; o2 < 64; o2 <<= 1) {
+      const int y = __shfl_up(x, o2);
+      if (ln >= o2) x += y;
+    }
+    if (ln == 63) wsum[wv] = x;
+    __syncthreads();
+    int run = x - local;
+    for (int w = 0; w < wv; ++w) run += wsum[w];
+    for (int i = 0; i < per; ++i)
+      if (b0 + i < B) {
+        pre[b0 + i] = run;
+        run += (cu_q[b0 + i + 1] - cu_q[b0 + i] + kTQ - 1) / kTQ;
+      }
+    if (t == 0) pre[B] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+    const bool live = tile_id < pre[B];
+    int lo = 0, hi = B;
+    while (live && hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pre[mid] <= tile_id) lo = mid; else hi = mid;
+    }
+    b = lo;
+    qt = live ? (pre[b + 1] - pre[b]) - 1 - (tile_id - pre[b]) : -1;
+    __syncthreads();  // the prefix sums are dead: the same LDS now receives K/V tiles
+  }
+  if (qt < 0) return;
   const int tok0 = cu_q[b];
   const int S = cu_q[b + 1] - tok0;
-  const int n_qt = (S + kTQ - 1) / kTQ;
-  const int qt = n_qt - 1 - qt_rev;
-  if (qt < 0) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
@@ -199,7 +238,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   stage_k(kbufs, k_cache, block_id(bt_row, kq, nblk_total), head_off, blk_stride, wave, lane);
   stage_v(vbufs, v_cache, __builtin_amdgcn_readfirstlane(block_id(bt_row, vq, nblk_total)), head_off, blk_stride,
           wave, lane);
-  int idk1 = block_id(bt_row, 4 + kq, nblk_total);
+  // K tile 1 goes out with tile 0 (both K buffers are free), which saves one memory round
+  // trip in the prologue
+  if (n_tiles > 1)
+    stage_k(kbufs + kKTileBytes, k_cache, block_id(bt_row, 4 + kq, nblk_total), head_off, blk_stride, wave, lane);
 
   // B operand of S^T: Q^T[d][row]; step t covers d = 16 t .. 16 t + 15
   bf16x8 qf[8];
@@ -231,8 +273,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     __syncthreads();
   }
 
-  // ---- prologue: K tile 1 on its way, scores of tile 0 --------------------------------------
-  if (n_tiles > 1) stage_k(kbufs + kKTileBytes, k_cache, idk1, head_off, blk_stride, wave, lane);
+  // ---- prologue: scores of tile 0 -----------------------------------------------------------
   int next_idk = block_id(bt_row, 8 + kq, nblk_total);     // K ids run two tiles ahead of the scores
   int next_idv = block_id(bt_row, 4 + vq, nblk_total);     // V ids one tile ahead
   f32x16 sa[2], sb[2];  // scores of the current / next tile, roles alternate
@@ -396,16 +437,17 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   }
 }
 
-hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t /*T*/,
-                               int32_t max_q_len, hipStream_t s) {
+hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
+                               int32_t /*max_q_len*/, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  const int n_qt_max = (max_q_len + kTQ - 1) / kTQ;
-  const int64_t n_wg = (int64_t)a.B * n_qt_max * G * a.Hkv;
+  // sum over sequences of ceil(S_b / kTQ) <= T / kTQ + (number of non-empty sequences)
+  const int64_t max_tiles = (int64_t)T / kTQ + (a.B < T ? a.B : T);
+  const int64_t n_wg = max_tiles * G * a.Hkv;
   if (n_wg <= 0) return hipSuccess;
   if (n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q,
                      (const char*)a.k_cache, (const char*)a.v_cache, cu_q, ctx_before, a.block_table, a.bt_stride,
-                     (uint16_t*)a.out, a.lse, a.B, a.Hq, a.Hkv, G, n_qt_max, a.scale_log2e);
+                     (uint16_t*)a.out, a.lse, a.B, a.Hq, a.Hkv, G, a.scale_log2e);
   return hipGetLastError();
 }
 

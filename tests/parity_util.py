@@ -107,9 +107,9 @@ def compare(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None):
     already miss the exact one by up to 0.0078 (|o| < 4) or 0.0156 (|o| < 8); such elements
     (a handful: short contexts, where the output is close to a single large V entry) are
     held to one bf16 spacing of the exact value instead.  Their count is printed."""
+    if rows is not None:   # select on the device first: full outputs can be gigabytes
+        got = got[torch.as_tensor(np.asarray(rows), dtype=torch.long, device=got.device)]
     g = got.detach().double().cpu().numpy()
-    if rows is not None:
-        g = g[rows]
     assert g.shape == ref.shape, (g.shape, ref.shape)
     assert np.all(np.isfinite(g)), f"{name}: non-finite values in the GPU output"
     err = np.abs(g - ref)
@@ -128,9 +128,9 @@ def compare(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None):
 
 
 def compare_lse(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None):
-    g = got.detach().double().cpu().numpy()
     if rows is not None:
-        g = g[rows]
+        got = got[torch.as_tensor(np.asarray(rows), dtype=torch.long, device=got.device)]
+    g = got.detach().double().cpu().numpy()
     err = float(np.abs(g - ref).max()) if ref.size else 0.0
     say(f"  {name}: lse max-abs {err:.3e} (<= {LSE_TOL[dtype]:g})")
     assert err <= LSE_TOL[dtype], f"{name}: lse error {err:.3e}"

@@ -1,0 +1,117 @@
+"""GPU parity at the full sizes of the benchmark workloads (one layer each, in the launch
+configuration bench.py times): the 30B- and 70B-scale decode batches in full, the prefill
+batches on sampled query rows the oracle computes one by one, and the 70B temporal-
+disaggregation switch (resident decode batch, prefill burst into the same pool, decode steps
+with the union).  Caches are compared bit for bit over the whole pool after every append."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2504_18154_amd import workloads as wl
+from tests.parity_util import Layer, compare, compare_lse, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _stream(model, T, seed):
+    """K/V token stream drawn on the GPU (fast at these sizes); the same bits go to the oracle."""
+    k = wl.randn((T, model.Hkv, model.D), model.dtype, seed, device="cuda")
+    v = wl.randn((T, model.Hkv, model.D), model.dtype, seed + 1, device="cuda")
+    return k, v
+
+
+def _sample_rows(rng, q_len, extra=32):
+    """Rows {0, 1, 15, 16, S-2, S-1} plus `extra` random ones per sequence, grouped by sequence."""
+    start, tok, pos = [0], [], []
+    cu = wl.cu_from_lengths(q_len)
+    for b, S in enumerate(q_len):
+        rows = {0, 1, 15, 16, S // 2, S - 2, S - 1} | set(rng.integers(0, S, size=extra).tolist())
+        rows = sorted(r for r in rows if 0 <= r < S)
+        tok += [int(cu[b]) + r for r in rows]
+        pos += rows
+        start.append(len(tok))
+    return np.asarray(start, np.int32), np.asarray(tok, np.int32), np.asarray(pos, np.int32)
+
+
+def _decode_full(db: wl.DecodeBatch, name):
+    model = db.model
+    say(f"{name}: B={db.B}, {int(db.ctx_len.sum())} cached tokens, pool {db.num_blocks} blocks")
+    layer = Layer(model, db.num_blocks, db.B, db.block_table.shape[1])
+    k, v = _stream(model, int(db.ctx_len.sum()), db.seed + 1)
+    layer.append(k, v, wl.cu_from_lengths(db.ctx_len), np.zeros(db.B, np.int32), db.block_table)
+    layer.assert_cache_bit_exact()
+    q = wl.randn((db.B, model.Hq, model.D), model.dtype, db.seed + 3, device="cuda")
+    out, lse = layer.decode_gpu(q, db.block_table, db.ctx_len)
+    ref, ref_lse = layer.decode_oracle(q, db.block_table, db.ctx_len)
+    compare(f"{name} decode", out, ref, "bf16")
+    compare_lse(f"{name} decode", lse, ref_lse, "bf16")
+    out2, _ = layer.decode_gpu(q, db.block_table, db.ctx_len)
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "not run-to-run deterministic"
+    layer.close()
+
+
+def test_config2_decode_30b_one_layer_full():
+    _decode_full(wl.config2_decode_30b(), "config index 1 (30B decode)")
+
+
+def test_config4_decode_70b_one_layer_full():
+    _decode_full(wl.config4_decode_70b(), "config index 3 (70B decode)")
+
+
+def test_config3_prefill_30b_one_layer_sampled_rows():
+    pb = wl.config3_prefill_30b()
+    model = pb.model
+    say(f"config index 2 (30B prefill): lengths {list(map(int, pb.q_len))}")
+    layer = Layer(model, pb.num_blocks, pb.B, pb.block_table.shape[1])
+    k, v = _stream(model, pb.T, pb.seed + 4)
+    q = wl.randn((pb.T, model.Hq, model.D), "bf16", pb.seed + 3, device="cuda")
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table, max_new_len=pb.max_q_len)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table, max_q_len=pb.max_q_len)
+    start, tok, pos = _sample_rows(wl.rng_for(1), pb.q_len)
+    ref, ref_lse = orc.attn_rows(layer.shape, wl.to_bits(q), layer.okc, layer.ovc, pb.block_table, start, tok, pos)
+    compare("prefill (sampled rows)", out, ref, "bf16", rows=tok)
+    compare_lse("prefill (sampled rows)", lse, ref_lse, "bf16", rows=tok)
+    layer.close()
+
+
+def test_config5_switch_70b_one_layer():
+    """Resident decode sequences, then a prefill-only burst of 8 x 8192 tokens appended into the
+    same pool, then decode-only steps in which the new sequences join the resident ones."""
+    model = wl.M70B
+    resident, q_len, table, nb = wl.config5_switch_70b()
+    nres, nnew = len(resident), len(q_len)
+    B = nres + nnew
+    say(f"config index 4 (70B switch): {nres} resident + {nnew} x {int(q_len[0])} tokens, pool {nb} blocks")
+    layer = Layer(model, nb, B, table.shape[1])
+    # resident contexts (the state left by earlier phases)
+    k, v = _stream(model, int(resident.sum()), 501)
+    layer.append(k, v, wl.cu_from_lengths(resident), np.zeros(nres, np.int32), table[:nres])
+    # prefill-only burst
+    cu = wl.cu_from_lengths(q_len)
+    T = int(cu[-1])
+    k, v = _stream(model, T, 503)
+    q = wl.randn((T, model.Hq, model.D), "bf16", 505, device="cuda")
+    zeros = np.zeros(nnew, np.int32)
+    layer.append(k, v, cu, zeros, table[nres:], max_new_len=int(q_len.max()))
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, cu, zeros, table[nres:], max_q_len=int(q_len.max()))
+    start, tok, pos = _sample_rows(wl.rng_for(2), q_len)
+    ref, ref_lse = orc.attn_rows(layer.shape, wl.to_bits(q), layer.okc, layer.ovc, table[nres:], start, tok, pos)
+    compare("burst prefill (sampled rows)", out, ref, "bf16", rows=tok)
+    compare_lse("burst prefill (sampled rows)", lse, ref_lse, "bf16", rows=tok)
+    # decode-only steps with all 200 sequences
+    ctx = np.concatenate([resident, q_len]).astype(np.int32)
+    ones = wl.cu_from_lengths([1] * B)
+    for step in range(3):
+        kn, vn = _stream(model, B, 600 + 10 * step)
+        qd = wl.randn((B, model.Hq, model.D), "bf16", 605 + 10 * step, device="cuda")
+        layer.append(kn, vn, ones, ctx, table, max_new_len=1)
+        ctx = ctx + 1
+        out, lse = layer.decode_gpu(qd, table, ctx)
+        ref, ref_lse = layer.decode_oracle(qd, table, ctx)
+        compare(f"decode step {step}", out, ref, "bf16")
+        compare_lse(f"decode step {step}", lse, ref_lse, "bf16")
+    layer.assert_cache_bit_exact()
+    layer.close()
