@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split size (tuning)")
     ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
                     help="run only one phase (profiling runs; the default is the full step)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no cross-GPU exchange step); "
@@ -148,6 +150,12 @@ def main() -> int:
 
     for _ in range(args.warmup):
         step()
+    if args.calibration_copy:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)   # 1 GiB read + 1 GiB written by a plain copy kernel
+        torch.cuda.synchronize()
+        del src, dst
     for c in (dctx, pctx):
         c.set_option(binding.OPT_PROFILE, 1)
         c.profile_reset()
@@ -188,6 +196,15 @@ def main() -> int:
             "prefill_prompts": pb.B, "prefill_tokens": pb.T, "prefill_lengths": [int(x) for x in pb.q_len],
         },
     }
+    def measured_traffic(kernel):
+        """HBM bytes per launch from the committed rocprofv3 --pmc runs (profiles/traffic.json), or None."""
+        try:
+            with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+                t = json.load(f).get(kernel)
+            return None if t is None else t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
+        except (OSError, ValueError, KeyError):
+            return None
+
     if do_dec:
         # phase time includes the one-token appends and the merge kernels: whole decode phase
         res["value"] = rate(dec_bytes_layer * layers, dec_ms) / 1e9
@@ -199,7 +216,8 @@ def main() -> int:
         avg_ms = k_dec_ms / max(k_dec_n, 1)
         a = rate(dec_bytes_layer, avg_ms) / 1e9
         res["roofline"] = {"kernel": "decode_mfma_kernel", "bound": "hbm", "achieved": a, "peak": acc.PEAK_HBM_GBPS,
-                           "unit": "GB/s", "frac": a / acc.PEAK_HBM_GBPS, "traffic": None,
+                           "unit": "GB/s", "frac": a / acc.PEAK_HBM_GBPS,
+                           "traffic": measured_traffic("decode_mfma_kernel") if layers == model.layers else None,
                            "avg_launch_us": avg_ms * 1e3, "launches": k_dec_n,
                            "algorithmic_bytes_per_launch": dec_bytes_layer}
     if do_pre:
@@ -212,7 +230,8 @@ def main() -> int:
             "frac_of_bf16_peak": tf / acc.PEAK_BF16_TFLOPS,
             "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": ktf,
                          "peak": acc.PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ktf / acc.PEAK_BF16_TFLOPS,
-                         "traffic": None, "avg_launch_us": avg_ms * 1e3, "launches": k_pre_n,
+                         "traffic": measured_traffic("prefill_mfma_kernel") if layers == model.layers else None,
+                         "avg_launch_us": avg_ms * 1e3, "launches": k_pre_n,
                          "algorithmic_flops_per_launch": pre_flops_layer},
             "append": {"GBps": rate(pre_app_bytes_layer, app_ms) / 1e9, "avg_launch_us": app_ms * 1e3,
                        "frac_of_hbm_peak": rate(pre_app_bytes_layer, app_ms) / 1e9 / acc.PEAK_HBM_GBPS},
@@ -228,14 +247,16 @@ def main() -> int:
         orc.kv_append(shape, okc, ovc, wl.to_bits(stream_k), wl.to_bits(stream_v), wl.cu_from_lengths(db.ctx_len),
                       np.zeros(db.B, dtype=np.int32), db.block_table)
         qh = wl.to_bits(d_q)
-        t0 = time.perf_counter()
-        ref, _ = orc.attn_decode(shape, qh, okc, ovc, db.block_table, db.ctx_len)
-        cpu_s = time.perf_counter() - t0
+        reps, t0 = 0, time.perf_counter()
+        while reps < 3 or time.perf_counter() - t0 < 1.5:   # ~1.5 s on all host cores
+            ref, _ = orc.attn_decode(shape, qh, okc, ovc, db.block_table, db.ctx_len)
+            reps += 1
+        cpu_s = (time.perf_counter() - t0) / reps
         err = np.abs(d_out[0].double().cpu().numpy() - ref)
         res["cpu_baseline"] = {
             "value": dec_bytes_layer / cpu_s / 1e9, "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"one full layer of the decode batch (128 seqs, {int(db.ctx_len.sum())} cached tokens), "
-                      f"fp64, {cpu_s:.2f} s",
+                      f"fp64, {reps} repetitions, {cpu_s:.3f} s each",
             "seconds": cpu_s,
             "gpu_vs_oracle_layer0_max_abs": float(err.max()), "gpu_vs_oracle_layer0_mean_abs": float(err.mean()),
         }

@@ -301,7 +301,9 @@ int ecoserve_attn_decode(ecoserve_ctx* c, const void* q, const void* k_cache, co
   if (use_mfma(c)) {
     {
       ProfileScope prof(c, ECOSERVE_KERNEL_DECODE, s);
-      e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len, c->num_cu, c->ws_acc, c->ws_ml, c->ws_meta,
+      e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len,
+                             c->num_cu * kDecodeWgsPerCu,
+                             c->ws_acc, c->ws_ml, c->ws_meta,
                              c->ws_splits, s);
     }
     if (e != hipSuccess) return ECOSERVE_EHIP;

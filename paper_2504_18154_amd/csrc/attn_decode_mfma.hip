@@ -9,7 +9,8 @@
 // of one (sequence, K/V head): 4 KiB of K and 4 KiB of V serving all G query heads of the
 // group.  Units are numbered sequence-major, then K/V head, then logical block, and the
 // numbering is cut into equal chunks of C units, one chunk per wavefront of a persistent
-// grid (2 workgroups of 4 wavefronts per CU).  Context lengths live on the device, so every
+// grid (one workgroup of 4 wavefronts per CU: one wavefront per SIMD, which is also the oldest
+// and so never starved by the memory pipeline's oldest-first arbitration).  Context lengths live on the device, so every
 // workgroup derives the numbering itself from a prefix sum over the batch (a few hundred
 // integers).  All wavefronts therefore stream the same number of bytes whatever the mix of
 // context lengths, start together and finish together.  A chunk may cover the tail of one
@@ -95,8 +96,9 @@ __device__ __forceinline__ void process_block(KVFrag& f, const bf16x8 (&qf)[4], 
 }
 
 // Exclusive prefix sums of the per-sequence block counts into LDS: pre[b] = blocks of
-// sequences 0..b-1, pre[B] = all.  Called by all 256 threads.
-__device__ __forceinline__ void scan_block_counts(int* pre, int* wsum, const int32_t* __restrict__ ctx_len, int B) {
+// sequences 0..b-1, pre[B] = all; lens[b] = context length.  Called by all 256 threads.
+__device__ __forceinline__ void scan_block_counts(int* pre, int* lens, int* wsum, const int32_t* __restrict__ ctx_len,
+                                                  int B) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per = (B + kWaves * 64 - 1) / (kWaves * 64);
   const int b0 = tid * per;
@@ -115,8 +117,10 @@ __device__ __forceinline__ void scan_block_counts(int* pre, int* wsum, const int
   for (int w = 0; w < wave; ++w) run += wsum[w];
   for (int i = 0; i < per; ++i)
     if (b0 + i < B) {
+      const int L = ctx_len[b0 + i];
+      lens[b0 + i] = L;
       pre[b0 + i] = run;
-      run += (ctx_len[b0 + i] + 15) >> 4;
+      run += (L + 15) >> 4;
     }
   if (tid == 0) pre[B] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
   __syncthreads();
@@ -129,14 +133,15 @@ __device__ __forceinline__ long long chunk_units(long long U, int n_waves, int c
   return c < kMinSplitTokens / kBlockSize ? kMinSplitTokens / kBlockSize : c;
 }
 
-__global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
+__global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
     int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, int B, int Hq, int Hkv, int G, float scale_log2e) {
   __shared__ int pre[kMaxBatch + 1];
+  __shared__ int lens[kMaxBatch];
   __shared__ int wsum[kWaves];
-  scan_block_counts(pre, wsum, ctx_len, B);
+  scan_block_counts(pre, lens, wsum, ctx_len, B);
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, quad = lane >> 4;
@@ -149,50 +154,82 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
     if (threadIdx.x == 0) ws_meta[0] = (int)C;
   }
   const int gw = blockIdx.x * kWaves + wave;
-  long long u = (long long)gw * C;
-  const long long u_end = min(U, u + C);
+  const long long u_begin = (long long)gw * C;
+  const long long u_end = min(U, u_begin + C);
   const size_t blk_stride = (size_t)Hkv * 4096;
+  if (u_begin >= u_end) return;
 
-  while (u < u_end) {
-    // locate the (sequence, head, block) of unit u: largest b with pre[b] <= u / Hkv
-    const int key = (int)(u / Hkv);
+  // A piece: the blocks [blk0, blk0 + n) of one (sequence b, K/V head g) that fall into this
+  // wavefront's chunk.  Everything a piece needs before its first K/V load - where it is
+  // (LDS only), its query fragments and its first 64 block ids - is fetched while the
+  // previous piece is still streaming, so a change of piece costs one memory round trip
+  // (the refill of the block pipeline) instead of three.
+  struct Piece {
+    int b, g, blk0, n, nb, L;
+    long long seg_u0;
+  };
+  auto locate = [&](long long u) {
+    Piece p;
+    const int key = (int)(u / Hkv);  // largest b with pre[b] <= u / Hkv
     int lo = 0, hi = B;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
       if (pre[mid] <= key) lo = mid; else hi = mid;
     }
-    const int b = lo;
-    const int nb = pre[b + 1] - pre[b];                    // blocks of this sequence
-    const long long seq_u0 = (long long)pre[b] * Hkv;
-    const int g = (int)((u - seq_u0) / nb);
-    const long long seg_u0 = seq_u0 + (long long)g * nb;   // first unit of (b, g)
-    const int blk0 = (int)(u - seg_u0);
-    const int n_piece = (int)(min(u_end, seg_u0 + nb) - u);
-    const int L = ctx_len[b];
-
-    // B operand of S^T: Q^T[d][head], heads beyond the group are zero columns
-    bf16x8 qf[4];
-    {
-      const uint16_t* qrow = q + ((size_t)b * Hq + (size_t)g * G + col) * 128;
+    p.b = lo;
+    p.nb = pre[lo + 1] - pre[lo];
+    const long long seq_u0 = (long long)pre[lo] * Hkv;
+    p.g = (int)((u - seq_u0) / p.nb);
+    p.seg_u0 = seq_u0 + (long long)p.g * p.nb;
+    p.blk0 = (int)(u - p.seg_u0);
+    p.n = (int)(min(u_end, p.seg_u0 + p.nb) - u);
+    p.L = lens[lo];
+    return p;
+  };
+  // B operand of S^T: Q^T[d][head], heads beyond the group are zero columns
+  auto load_q = [&](bf16x8 (&qf)[4], const Piece& p) {
+    const uint16_t* qrow = q + ((size_t)p.b * Hq + (size_t)p.g * G + col) * 128;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-        qf[kk] = col < G ? *reinterpret_cast<const bf16x8*>(qrow + kk * 32 + quad * 8) : z;
-      }
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      qf[kk] = col < G ? *reinterpret_cast<const bf16x8*>(qrow + kk * 32 + quad * 8) : z;
     }
-    const size_t head_off = (size_t)g * 4096;
-    const int32_t* bt_row = block_table + (size_t)b * bt_stride;
+  };
+  // physical ids of up to 64 consecutive logical blocks of a piece, lane i holding block base + i
+  auto load_ids = [&](const Piece& p, int base) {
+    int id = 0;
+    if (base + lane < p.n) id = block_table[(size_t)p.b * bt_stride + p.blk0 + base + lane];
+    return id;
+  };
+
+  long long u = u_begin;
+  Piece cur = locate(u);
+  bf16x8 qf[4];
+  load_q(qf, cur);
+  int ids = load_ids(cur, 0);
+  for (;;) {
+    const long long u_next = u + cur.n;
+    const bool has_next = u_next < u_end;
+    Piece nxt = cur;
+    bf16x8 qn[4];
+    int ids_n = 0;
+    if (has_next) {
+      nxt = locate(u_next);
+      load_q(qn, nxt);
+      ids_n = load_ids(nxt, 0);
+    }
+    const size_t head_off = (size_t)cur.g * 4096;
+    const int L = cur.L;
 
     f32x4 acc[8];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.f;
 
-    for (int base = 0; base < n_piece; base += 64) {
-      // physical ids of up to 64 consecutive logical blocks, lane i holding block base + i
-      const int n = min(64, n_piece - base);
-      int my_id = 0;
-      if (lane < n) my_id = bt_row[blk0 + base + lane];
+    for (int base = 0; base < cur.n; base += 64) {
+      const int n = min(64, cur.n - base);
+      const int my_id = ids;
+      if (base + 64 < cur.n) ids = load_ids(cur, base + 64);  // ids of the following 64 blocks, early
       // Register pipeline three blocks deep.  Loads are issued unconditionally with the
       // index clamped to the last block (a harmless re-read that hits in cache), so the
       // number of loads in flight is the same on every path and waits stay precise.
@@ -201,7 +238,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
         const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, ii) * blk_stride + head_off;
         load_block(f, k_cache + off, v_cache + off, lane, col, quad);
       };
-      auto tail_of = [&](int i) { return L - ((blk0 + base + i) << 4); };  // >= 16 except in the sequence's last block
+      auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // >= 16 except in the sequence's last block
       KVFrag f0, f1, f2;
       issue(f0, 0);
       issue(f1, 1);
@@ -221,10 +258,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     if (col < G) {
-      const int h = g * G + col;
-      if (n_piece == nb) {  // the whole (sequence, head): final
+      const int h = cur.g * G + col;
+      if (cur.n == cur.nb) {  // the whole (sequence, head): final
         const float inv = 1.f / l;
-        uint16_t* orow = out + ((size_t)b * Hq + h) * 128;
+        uint16_t* orow = out + ((size_t)cur.b * Hq + h) * 128;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
           u32x2 w;
@@ -232,10 +269,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
           w[1] = (uint32_t)float_to_bf16_bits(acc[dt][2] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][3] * inv) << 16);
           *reinterpret_cast<u32x2*>(orow + dt * 16 + 4 * quad) = w;
         }
-        if (lse && quad == 0) lse[(size_t)b * Hq + h] = (m + log2f(l)) * kLn2;
+        if (lse && quad == 0) lse[(size_t)cur.b * Hq + h] = (m + log2f(l)) * kLn2;
       } else {
-        const int split = gw - (int)(seg_u0 / C);
-        const size_t slot = ((size_t)b * Hq + h) * ws_splits + split;
+        const int split = gw - (int)(cur.seg_u0 / C);
+        const size_t slot = ((size_t)cur.b * Hq + h) * ws_splits + split;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
         if (quad == 0) {
@@ -244,7 +281,12 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(
         }
       }
     }
-    u += n_piece;
+    if (!has_next) break;
+    u = u_next;
+    cur = nxt;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) qf[kk] = qn[kk];
+    ids = ids_n;
   }
 }
 
@@ -281,10 +323,10 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
 }
 
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
-                              int32_t num_cu, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
-                              hipStream_t s) {
+                              int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta,
+                              int32_t ws_splits, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  int n_wg = 2 * num_cu;  // persistent: two workgroups per CU (register budget of the pipeline)
+  int n_wg = n_persistent_wgs;
   int c_forced = 0;
   if (split_tokens > 0) {
     // forced chunk size: the grid must cover the largest possible number of units

@@ -14,6 +14,7 @@ constexpr int kBlockSize = 16;        // tokens per cache block (the only suppor
 constexpr int kMaxGroup = 16;         // largest supported Hq / Hkv
 constexpr int kMinSplitTokens = 64;   // smallest decode split
 constexpr int kMaxSplitTokens = 4096; // largest forced decode split
+constexpr int kDecodeWgsPerCu = 1;    // persistent decode grid: workgroups per CU (one wavefront per SIMD)
 constexpr int kMaxBatch = 4096;       // largest max_batch a context accepts (batch prefix sums live in LDS)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -81,7 +82,7 @@ hipError_t launch_decode_merge(const AttnArgs& a, const int32_t* ctx_len, int32_
 // attn_decode_mfma.hip: bf16, D = 128
 // (split_tokens 0 = equal share per wavefront of the persistent grid; > 0 forces the chunk size)
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
-                              int32_t num_cu, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
+                              int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
                               hipStream_t s);
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
                                     const int32_t* ws_meta, int32_t ws_splits, hipStream_t s);
