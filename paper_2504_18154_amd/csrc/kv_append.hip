@@ -59,7 +59,7 @@ __device__ __forceinline__ void scan_touched_blocks(int* pre, int* wsum, const i
   __syncthreads();
 }
 
-template <typename E>
+template <typename E, bool kOneToken>
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
                                                                     const E* __restrict__ k_new,
                                                                     const E* __restrict__ v_new,
@@ -72,18 +72,28 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
   __shared__ int pre[kMaxBatch + 1];
   __shared__ int wsum[kAppendThreads / 64];
   __shared__ __attribute__((aligned(16))) E vt[16][256 + X];  // staged V rows (D <= 256), padded
-  scan_touched_blocks(pre, wsum, cu_q, ctx_before, B);
-
-  const int unit = blockIdx.x;  // destination block number within the batch
-  if (unit >= pre[B]) return;
-  int lo_b = 0, hi_b = B;
-  while (hi_b - lo_b > 1) {
-    const int mid = (lo_b + hi_b) >> 1;
-    if (pre[mid] <= unit) lo_b = mid; else hi_b = mid;
+  int b, first_unit;
+  if (kOneToken) {
+    // at most one new token per sequence (decode step): sequence b touches at most one block,
+    // so workgroup b serves sequence b and no numbering is needed
+    b = blockIdx.x;
+    first_unit = b;
+    if (cu_q[b + 1] - cu_q[b] <= 0) return;
+  } else {
+    scan_touched_blocks(pre, wsum, cu_q, ctx_before, B);
+    if ((int)blockIdx.x >= pre[B]) return;
+    int lo_b = 0, hi_b = B;
+    while (hi_b - lo_b > 1) {
+      const int mid = (lo_b + hi_b) >> 1;
+      if (pre[mid] <= (int)blockIdx.x) lo_b = mid; else hi_b = mid;
+    }
+    b = lo_b;
+    first_unit = pre[b];
   }
-  const int b = lo_b, g = blockIdx.y, tid = threadIdx.x;
+  const int unit = blockIdx.x;  // destination block number within the batch
+  const int g = blockIdx.y, tid = threadIdx.x;
   const int tok0 = cu_q[b], S = cu_q[b + 1] - tok0, cb = ctx_before[b];
-  const int j = (cb >> 4) + (unit - pre[b]);          // logical block of the sequence
+  const int j = (cb >> 4) + (unit - first_unit);      // logical block of the sequence
   const int lo = max(0, cb - (j << 4));               // addressed slots [lo, hi) of this block
   const int hi = min(16, cb + S - (j << 4));
   const int t_slot0 = tok0 + (j << 4) - cb;           // packed token index of slot 0 (may be < tok0)
@@ -125,23 +135,36 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
   }
 }
 
+template <typename E>
+static void launch_typed(const ecoserve_layout& L, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
+                         const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
+                         int32_t bt_stride, int32_t B, int32_t T, int32_t max_new_len, hipStream_t s) {
+  if (max_new_len <= 1) {
+    const dim3 grid((unsigned)B, (unsigned)L.num_kv_heads);
+    hipLaunchKernelGGL((kv_append_kernel<E, true>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
+                       (const E*)k_new, (const E*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
+                       L.num_kv_heads, L.head_dim);
+  } else {
+    // a sequence with S new tokens touches at most S/16 + 2 blocks (ragged at both ends), and none if S == 0
+    const int64_t max_units = (int64_t)T / 16 + 2 * (int64_t)(B < T ? B : T);
+    const dim3 grid((unsigned)max_units, (unsigned)L.num_kv_heads);
+    hipLaunchKernelGGL((kv_append_kernel<E, false>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
+                       (const E*)k_new, (const E*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
+                       L.num_kv_heads, L.head_dim);
+  }
+}
+
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
                             const void* v_new, const int32_t* cu_q, const int32_t* ctx_before,
                             const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
-                            int32_t /*max_new_len*/, hipStream_t s) {
+                            int32_t max_new_len, hipStream_t s) {
   const ecoserve_layout& L = ctx->lay;
-  // a sequence with S new tokens touches at most S/16 + 2 blocks (ragged at both ends), and none if S == 0
-  const int64_t max_units = (int64_t)T / 16 + 2 * (int64_t)(B < T ? B : T);
-  const dim3 grid((unsigned)max_units, (unsigned)L.num_kv_heads);
-  if (L.dtype == ECOSERVE_BF16) {
-    hipLaunchKernelGGL(kv_append_kernel<uint16_t>, grid, dim3(kAppendThreads), 0, s, (uint16_t*)k_cache,
-                       (uint16_t*)v_cache, (const uint16_t*)k_new, (const uint16_t*)v_new, cu_q, ctx_before,
-                       block_table, bt_stride, B, L.num_kv_heads, L.head_dim);
-  } else {
-    hipLaunchKernelGGL(kv_append_kernel<float>, grid, dim3(kAppendThreads), 0, s, (float*)k_cache, (float*)v_cache,
-                       (const float*)k_new, (const float*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
-                       L.num_kv_heads, L.head_dim);
-  }
+  if (L.dtype == ECOSERVE_BF16)
+    launch_typed<uint16_t>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T,
+                           max_new_len, s);
+  else
+    launch_typed<float>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T,
+                        max_new_len, s);
   return hipGetLastError();
 }
 
