@@ -19,7 +19,7 @@
 //
 // Per piece, the wavefront streams whole cache blocks with fully coalesced per-lane loads
 // that land directly in MFMA operand layout - no LDS staging, no barriers, a register
-// pipeline three blocks deep, physical block ids prefetched 64 at a time into one VGPR:
+// pipeline kDepth blocks deep, physical block ids prefetched 64 at a time into one VGPR:
 //   scores  S^T[token][head] = K . Q^T   v_mfma_f32_16x16x32_bf16 (heads padded to 16 columns)
 //   online softmax per column in the exp2 domain; the four 16-lane groups hold different
 //   tokens of the same head, their maxima are combined with wavefront shuffles
@@ -38,6 +38,10 @@
 namespace eco {
 
 constexpr int kWaves = 4;
+#ifndef ECO_DECODE_DEPTH
+#define ECO_DECODE_DEPTH 4
+#endif
+constexpr int kDepth = ECO_DECODE_DEPTH;  // cache blocks in flight per wavefront (8 KiB each)
 
 struct KVFrag {
   bf16x8 k[4];   // K block: unit (4*kk + quad, token = col)  ->  A operand of S^T step kk
@@ -230,7 +234,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
       const int n = min(64, cur.n - base);
       const int my_id = ids;
       if (base + 64 < cur.n) ids = load_ids(cur, base + 64);  // ids of the following 64 blocks, early
-      // Register pipeline three blocks deep.  Loads are issued unconditionally with the
+      // Register pipeline kDepth blocks deep.  Loads are issued unconditionally with the
       // index clamped to the last block (a harmless re-read that hits in cache), so the
       // number of loads in flight is the same on every path and waits stay precise.
       auto issue = [&](KVFrag& f, int i) {
@@ -239,18 +243,19 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
         load_block(f, k_cache + off, v_cache + off, lane, col, quad);
       };
       auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // >= 16 except in the sequence's last block
-      KVFrag f0, f1, f2;
-      issue(f0, 0);
-      issue(f1, 1);
-      for (int i = 0; i < n; i += 3) {
-        issue(f2, i + 2);
-        process_block(f0, qf, acc, m, l, tail_of(i), quad, scale_log2e);
-        if (i + 1 >= n) break;
-        issue(f0, i + 3);
-        process_block(f1, qf, acc, m, l, tail_of(i + 1), quad, scale_log2e);
-        if (i + 2 >= n) break;
-        issue(f1, i + 4);
-        process_block(f2, qf, acc, m, l, tail_of(i + 2), quad, scale_log2e);
+      KVFrag f[kDepth];
+#pragma unroll
+      for (int d = 0; d < kDepth - 1; ++d) issue(f[d], d);
+      for (int i = 0; i < n; i += kDepth) {
+        bool done = false;
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+          if (!done) {
+            issue(f[(d + kDepth - 1) % kDepth], i + d + kDepth - 1);
+            process_block(f[d], qf, acc, m, l, tail_of(i + d), quad, scale_log2e);
+            done = i + d + 1 >= n;
+          }
+        }
       }
     }
 
