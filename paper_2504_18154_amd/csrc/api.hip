@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -56,9 +57,11 @@ int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
   if (c->ws_acc) (void)hipFree(c->ws_acc);
   if (c->ws_ml) (void)hipFree(c->ws_ml);
   if (c->ws_meta) (void)hipFree(c->ws_meta);
+  if (c->ws_plan) (void)hipFree(c->ws_plan);
   c->ws_acc = nullptr;
   c->ws_ml = nullptr;
   c->ws_meta = nullptr;
+  c->ws_plan = nullptr;
   c->ws_splits = 0;
   c->ws_bytes = 0;
   const size_t slots = (size_t)c->max_batch * c->lay.num_q_heads * splits;
@@ -67,17 +70,24 @@ int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
   if (slots == 0) return ECOSERVE_OK;
   if (hipMalloc(&c->ws_acc, acc_bytes) != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_ENOMEM; }
   const size_t meta_bytes = ((size_t)c->max_batch + 3) * sizeof(int32_t);
-  if (hipMalloc(&c->ws_ml, ml_bytes) != hipSuccess || hipMalloc(&c->ws_meta, meta_bytes) != hipSuccess) {
+  // a prefill batch cannot bring more new tokens than the pool holds
+  c->plan_tiles = prefill_plan_tiles(c->max_batch, (int32_t)std::min<int64_t>(
+                                                        (int64_t)c->lay.num_blocks * kBlockSize, 0x7fffffffLL));
+  const size_t plan_bytes = ((size_t)kPlanHeaderInts + (size_t)c->plan_tiles * kRecInts) * sizeof(int32_t);
+  if (hipMalloc(&c->ws_ml, ml_bytes) != hipSuccess || hipMalloc(&c->ws_meta, meta_bytes) != hipSuccess ||
+      hipMalloc(&c->ws_plan, plan_bytes) != hipSuccess) {
     (void)hipGetLastError();
     (void)hipFree(c->ws_acc);
     if (c->ws_ml) (void)hipFree(c->ws_ml);
+    if (c->ws_meta) (void)hipFree(c->ws_meta);
     c->ws_acc = nullptr;
     c->ws_ml = nullptr;
     c->ws_meta = nullptr;
+    c->ws_plan = nullptr;
     return ECOSERVE_ENOMEM;
   }
   c->ws_splits = splits;
-  c->ws_bytes = acc_bytes + ml_bytes + meta_bytes;
+  c->ws_bytes = acc_bytes + ml_bytes + meta_bytes + plan_bytes;
   return ECOSERVE_OK;
 }
 
@@ -181,6 +191,8 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   c->ws_acc = nullptr;
   c->ws_ml = nullptr;
   c->ws_meta = nullptr;
+  c->ws_plan = nullptr;
+  c->plan_tiles = 0;
   c->ws_splits = 0;
   c->ws_bytes = 0;
   for (int i = 0; i < 3; ++i) c->ev_used[i] = 0;
@@ -198,6 +210,7 @@ int ecoserve_destroy(ecoserve_ctx* c) {
   if (c->ws_acc) (void)hipFree(c->ws_acc);
   if (c->ws_ml) (void)hipFree(c->ws_ml);
   if (c->ws_meta) (void)hipFree(c->ws_meta);
+  if (c->ws_plan) (void)hipFree(c->ws_plan);
   for (int i = 0; i < 3; ++i)
     for (EventPair& e : c->ev[i]) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
   delete c;
@@ -268,15 +281,16 @@ int ecoserve_attn_prefill(ecoserve_ctx* c, const void* q, const void* k_cache, c
   if (B > c->max_batch || bt_stride <= 0 || max_q_len > T || max_q_len == 0) return ECOSERVE_EINVAL;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return ECOSERVE_EINVAL;
   if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return ECOSERVE_EINVAL;
+  if (prefill_plan_tiles(B, T) > c->plan_tiles) return ECOSERVE_EINVAL;  // more new tokens than the pool holds
   DeviceGuard guard(c->device);
   if (!guard.ok) return ECOSERVE_EHIP;
   hipStream_t s = (hipStream_t)stream;
   const AttnArgs a = make_args(c, q, k_cache, v_cache, block_table, bt_stride, out, lse, B);
   ProfileScope prof(c, ECOSERVE_KERNEL_PREFILL, s);
   hipError_t e;
-  if (use_mfma(c))
-    e = launch_prefill_mfma(a, cu_q, ctx_before, T, max_q_len, s);
-  else
+  if (use_mfma(c)) {
+    e = launch_prefill_mfma(a, cu_q, ctx_before, T, max_q_len, c->ws_plan, c->num_cu * kPrefillWgsPerCu, s);
+  } else
     e = launch_prefill_plain(a, cu_q, ctx_before, T, s);
   return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
 }

@@ -7,13 +7,18 @@
 // ctx_before[b] + i and sees keys 0..that position (a cached prefix is handled by the
 // same loop).
 //
-// Work decomposition: one workgroup (4 wavefronts) = 128 query rows of one query head;
-// each wavefront owns 32 rows; two workgroups share a CU so that one's softmax (VALU)
-// runs under the other's matrix work.  Workgroup ids are laid out so that consecutive ids
-// differ first in the K/V head (ids are dealt round-robin to the 8 XCDs, so with 8 K/V
-// heads each XCD's L2 holds one head's K/V), then in the query head of the group, then in
-// the query tile (heaviest, i.e. last, tile first), then in the sequence; only tiles that
-// exist are launched (plus a few surplus workgroups that exit at once).
+// Work decomposition: one work item = 128 query rows (a query tile) of one query head,
+// computed by one workgroup (4 wavefronts, 32 rows each).  A small plan kernel lists the
+// batch's query tiles, heaviest (most key steps) first; the attention kernel is persistent:
+// two workgroups per CU (one's softmax VALU work runs under the other's matrix work), each
+// taking items from the list until it is empty.  While an item's last key step is being
+// processed the workgroup already fetches the first K/V steps and the query rows of its next
+// item, so a change of item costs no memory round trip: with the short prompts of a
+// lognormal batch the start-up of a workgroup (tile lookup, block ids, first tiles, output
+// write-back) would otherwise take a fifth of the kernel's time.  Items are dealt so that
+// consecutive ones differ first in the K/V head and a workgroup prefers the items whose
+// index is congruent to its XCD (workgroup ids are dealt round-robin to the 8 XCDs): with 8
+// K/V heads each XCD's L2 holds one head's K/V.
 //
 // Per 64-key step the four 16-token cache blocks of K and of V go straight from global
 // memory into LDS (global_load ... lds, 16 bytes per lane, double buffered, one barrier per
@@ -40,16 +45,22 @@
 // Lane layout relied upon for 32x32x16 (lane = 32*half + col):
 //   A[row = col][k = 8*half .. +7],  B[k = 8*half .. +7][col],
 //   C[row = 8*(i/4) + 4*half + i%4][col], i = 0..15.
+#include <type_traits>
+
 #include "common.h"
 
 namespace eco {
 
-constexpr int kTQ = 128;                       // query rows per workgroup
+constexpr int kTQ = kPrefillTileRows;          // query rows per work item
 constexpr int kTK = 64;                        // keys per step
 constexpr int kKTileBytes = 16 * kTK * 16;     // [16 units][64 keys][16 B]
 constexpr int kVOctStride = 128 * 16 + 64;     // one 8-key octet: [128 d][16 B] + pad
 constexpr int kVTileBytes = 8 * kVOctStride;
 constexpr float kTau = 8.f;                    // lazy-rescale threshold, log2 units
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanBins = 4096;                // weight classes of the plan's counting sort
+constexpr int kQueues = 8;                     // work queues (a multiple of 8; more did not help)
+static_assert(kQueues % 8 == 0 && kQueues <= kPlanMaxQueues, "queues come in multiples of the XCD count");
 
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
@@ -110,13 +121,14 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // as two 32-key accumulators; the maximum is combined across the two lane halves.
 __device__ __forceinline__ float mask_and_max(f32x16 (&s)[2], int k0, int half, int pos, bool masked) {
   if (masked) {
+    // key index inside the step minus the lane-dependent part, against the bound moved the same
+    // way: the comparisons take literal constants and one register
+    const int bound = pos - k0 - half * 8;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = k0 + sub * 32 + (i >> 3) * 16 + half * 8 + (i & 7);
-        if (key > pos) s[sub][i] = -INFINITY;
-      }
+      for (int i = 0; i < 16; ++i)
+        if (sub * 32 + (i >> 3) * 16 + (i & 7) > bound) s[sub][i] = -INFINITY;
   }
   float bm = max3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
@@ -153,106 +165,240 @@ __device__ __forceinline__ void exp_tile(const f32x16& s, bf16x8 (&pf)[2], float
   l = l0 + l1;
 }
 
-__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
-    const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
-    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ ctx_before,
-    const int32_t* __restrict__ block_table, int bt_stride, uint16_t* __restrict__ out, float* __restrict__ lse,
-    int B, int Hq, int Hkv, int G, float scale_log2e) {
-  __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes];
-  static_assert((kMaxBatch + 1 + 4) * 4 <= 2 * kKTileBytes + 2 * kVTileBytes, "batch prefix sums must fit in the tile buffers");
-  char* const kbufs = smem;
-  char* const vbufs = smem + 2 * kKTileBytes;
-
-  // Query tiles of the whole batch are numbered sequence after sequence, last (heaviest)
-  // tile of a sequence first.  The grid covers an upper bound on their number that the host
-  // can compute; every workgroup finds its (sequence, tile) from a prefix sum over the batch,
-  // held in the LDS that the K/V buffers take over afterwards.
-  int wg = blockIdx.x;
-  const int g = wg % Hkv;  wg /= Hkv;
-  const int hg = wg % G;   wg /= G;
-  const int tile_id = wg;
-  int b, qt;
-  {
-    int* pre = reinterpret_cast<int*>(smem);            // [B + 1]
-    int* wsum = pre + kMaxBatch + 1;                    // [4]
-    const int t = threadIdx.x, ln = t & 63, wv = t >> 6;
-    const int per = (B + 255) / 256, b0 = t * per;
-    int local = 0;
-    for (int i = 0; i < per; ++i)
-      if (b0 + i < B) local += (cu_q[b0 + i + 1] - cu_q[b0 + i] + kTQ - 1) / kTQ;
+// ---- plan: the query tiles of a batch, heaviest first ------------------------------------------
+//
+// Plan layout (int32): [0] number of query tiles, [kPlanCounter0 + kPlanCounterStride * i] ticket
+// counter of work queue i (one cache line each), then from kPlanHeaderInts one record of kRecInts
+// per query tile:
+//   0 sequence, 1 tile inside the sequence, 2 first packed token of the sequence, 3 S,
+//   4 ctx_before, 5 number of 64-key steps, 8..19 physical ids of the sequence's first 12 blocks
+// (clamped to its last block), i.e. everything a workgroup needs to start on the tile with one
+// load.  Records are sorted by the number of key steps, largest first, with a counting sort
+// (tiles with kPlanBins - 1 or more steps share a class; the order inside a class is arbitrary).
+__global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_t* __restrict__ cu_q,
+                                                                    const int32_t* __restrict__ ctx_before,
+                                                                    const int32_t* __restrict__ block_table,
+                                                                    int bt_stride, int B, int n_main_wgs,
+                                                                    int32_t* __restrict__ plan) {
+  __shared__ int pre[kMaxBatch + 1];
+  __shared__ int bins[kPlanBins];
+  __shared__ int wsum[kPlanThreads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // exclusive prefix of one value per thread over the workgroup; `total` receives the sum
+  auto block_scan = [&](int local, int& total) -> int {
     int x = local;
 #pragma unroll
-    for (int o2 = 1; o2 < 64; o2 <<= 1) {
-      const int y = __shfl_up(x, o2);
-      if (ln >= o2) x += y;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(x, o);
+      if (lane >= o) x += y;
     }
-    if (ln == 63) wsum[wv] = x;
+    if (lane == 63) wsum[wave] = x;
     __syncthreads();
     int run = x - local;
-    for (int w = 0; w < wv; ++w) run += wsum[w];
-    for (int i = 0; i < per; ++i)
-      if (b0 + i < B) {
-        pre[b0 + i] = run;
-        run += (cu_q[b0 + i + 1] - cu_q[b0 + i] + kTQ - 1) / kTQ;
-      }
-    if (t == 0) pre[B] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    total = 0;
+    for (int w = 0; w < kPlanThreads / 64; ++w) {
+      if (w < wave) run += wsum[w];
+      total += wsum[w];
+    }
     __syncthreads();
-    const bool live = tile_id < pre[B];
+    return run;
+  };
+  auto tiles_of = [&](int b) { return (cu_q[b + 1] - cu_q[b] + kTQ - 1) / kTQ; };
+
+  const int per = (B + kPlanThreads - 1) / kPlanThreads, b0 = tid * per;
+  int local = 0;
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) local += tiles_of(b0 + i);
+  int n_tiles_all;
+  int run = block_scan(local, n_tiles_all);
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) {
+      pre[b0 + i] = run;
+      run += tiles_of(b0 + i);
+    }
+  if (tid == 0) pre[B] = n_tiles_all;
+  for (int i = tid; i < kPlanBins; i += kPlanThreads) bins[i] = 0;
+  __syncthreads();
+
+  // tile i of the batch (sequence after sequence) -> sequence, tile, key steps, weight class
+  auto locate = [&](int i, int& b, int& qt, int& steps) -> int {
     int lo = 0, hi = B;
-    while (live && hi - lo > 1) {
+    while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if (pre[mid] <= tile_id) lo = mid; else hi = mid;
+      if (pre[mid] <= i) lo = mid; else hi = mid;
     }
     b = lo;
-    qt = live ? (pre[b + 1] - pre[b]) - 1 - (tile_id - pre[b]) : -1;
-    __syncthreads();  // the prefix sums are dead: the same LDS now receives K/V tiles
+    qt = i - pre[b];
+    const int S = cu_q[b + 1] - cu_q[b];
+    const long long kv_end = (long long)ctx_before[b] + (long long)qt * kTQ + min(kTQ, S - qt * kTQ);
+    steps = (int)((kv_end + kTK - 1) / kTK);
+    return kPlanBins - 1 - min(steps, kPlanBins - 1);  // class 0 = heaviest
+  };
+  for (int i = tid; i < n_tiles_all; i += kPlanThreads) {
+    int b, qt, steps;
+    atomicAdd(&bins[locate(i, b, qt, steps)], 1);
   }
-  if (qt < 0) return;
-  const int tok0 = cu_q[b];
-  const int S = cu_q[b + 1] - tok0;
+  __syncthreads();
+  {
+    constexpr int kPer = kPlanBins / kPlanThreads;
+    int cnt[kPer], sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      cnt[i] = bins[tid * kPer + i];
+      sum += cnt[i];
+    }
+    int total;
+    int start = block_scan(sum, total);
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      bins[tid * kPer + i] = start;
+      start += cnt[i];
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < n_tiles_all; i += kPlanThreads) {
+    int b, qt, steps;
+    const int cls = locate(i, b, qt, steps);
+    int32_t* rec = plan + kPlanHeaderInts + (size_t)atomicAdd(&bins[cls], 1) * kRecInts;
+    const int cb = ctx_before[b], S = cu_q[b + 1] - cu_q[b];
+    const int nblk_total = (int)(((long long)cb + S + 15) >> 4);
+    rec[0] = b;
+    rec[1] = qt;
+    rec[2] = cu_q[b];
+    rec[3] = S;
+    rec[4] = cb;
+    rec[5] = steps;
+    rec[6] = 0;
+    rec[7] = 0;
+    for (int j = 0; j < 12; ++j) rec[8 + j] = block_table[(size_t)b * bt_stride + min(j, nblk_total - 1)];
+  }
+  if (tid == 0) plan[0] = n_tiles_all;
+  // each workgroup of the attention kernel owns the first two tickets of its queue outright
+  if (tid < kQueues) plan[kPlanCounter0 + kPlanCounterStride * tid] = 2 * ((n_main_wgs - tid + kQueues - 1) / kQueues);
+}
+
+// Wave-uniform description of one work item (a query tile of one query head).
+struct Item {
+  int tok0, S, cb, q0, g, h, n_tiles;
+  const int32_t* bt_row;
+  __device__ __forceinline__ int L_total() const { return cb + S; }
+  __device__ __forceinline__ int nblk_total() const { return (cb + S + 15) >> 4; }
+};
+
+// `rec` holds field l of the tile's plan record in lane l; g, h: the item's K/V and query head.
+__device__ __forceinline__ Item describe(int rec, int g, int h, const int32_t* __restrict__ block_table,
+                                         int bt_stride) {
+  Item t;
+  const int b = __builtin_amdgcn_readlane(rec, 0), qt = __builtin_amdgcn_readlane(rec, 1);
+  t.tok0 = __builtin_amdgcn_readlane(rec, 2);
+  t.S = __builtin_amdgcn_readlane(rec, 3);
+  t.cb = __builtin_amdgcn_readlane(rec, 4);
+  t.n_tiles = __builtin_amdgcn_readlane(rec, 5);
+  t.g = g;
+  t.h = h;
+  t.q0 = qt * kTQ;
+  t.bt_row = block_table + (size_t)b * bt_stride;
+  return t;
+}
+
+__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
+    const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
+    const int32_t* __restrict__ block_table, int bt_stride, uint16_t* __restrict__ out, float* __restrict__ lse,
+    int32_t* __restrict__ plan, int Hq, int Hkv, int G, Divisor div_heads, Divisor div_hkv, float scale_log2e) {
+  __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes + 16];
+  char* const kbufs = smem;
+  char* const vbufs = smem + 2 * kKTileBytes;
+  int* const slot = reinterpret_cast<int*>(smem + 2 * kKTileBytes + 2 * kVTileBytes);  // tickets from thread 0
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
-  const int h = g * G + hg;
-  const int cb = ctx_before[b];
-  const int L_total = cb + S;
-  const int nblk_total = (L_total + 15) >> 4;
-  const int q0 = qt * kTQ;
-  const int kv_end = cb + min(S, q0 + kTQ);            // keys [0, kv_end) are needed by this workgroup
-  const int n_tiles = (kv_end + kTK - 1) / kTK;
-  const int row = q0 + wave * 32 + col;                // this lane's query row inside the sequence
-  const bool row_valid = row < S;
-  const int pos = cb + row;                            // absolute position = causal bound
-  const int w_pmin = cb + q0 + wave * 32;              // smallest / largest bound in this wavefront
-  const int w_pmax = cb + min(S - 1, q0 + wave * 32 + 31);
-  const int n_w = min(n_tiles, w_pmax / kTK + 1);      // tiles not wholly above this wavefront's diagonal
-  const float c = scale_log2e;
-
-  const int32_t* bt_row = block_table + (size_t)b * bt_stride;
-  const size_t head_off = (size_t)g * 4096;
-  const size_t blk_stride = (size_t)Hkv * 4096;
   const int kq = lane >> 4;  // which block of a tile this lane copies for K
   const int vq = tid >> 6;   // ... and for V (= wave, kept in a VGPR so that the id is fetched with a vector
                              // load: an outstanding scalar load would force full waits on every LDS read)
+  const float c = scale_log2e;
+  const size_t blk_stride = (size_t)Hkv * 4096;
+  const int heads = G * Hkv;
+  const int n_flat = plan[0] * heads;
+  const int32_t* const recs = plan + kPlanHeaderInts;
+  // Work items are dealt to kQueues queues (item f belongs to queue f % kQueues) and workgroup w
+  // serves queue w % kQueues.  kQueues is a multiple of 8: workgroup ids are dealt round-robin to
+  // the 8 XCDs and with eight K/V heads item f reads K/V head f % 8, so an XCD's L2 sees one head's
+  // K/V.  The queues hold the same amount of work to within one item per weight class, and a
+  // workgroup whose queue is empty is done.  Taking from other queues, or from a pool shared by
+  // all, costs more than the imbalance it removes: atomics on one address are served one after the
+  // other, and hundreds of workgroups asking the same counter at the same moment wait tens of
+  // microseconds.
+  const int queue = blockIdx.x % kQueues;
+  int* const counter = plan + kPlanCounter0 + kPlanCounterStride * queue;
+  auto resolve = [&](int k) -> int {  // ticket k of the own queue -> item, -1 past the end
+    const int f = kQueues * k + queue;
+    return f < n_flat ? f : -1;
+  };
+  // item f is query head f % (G Hkv) of tile f / (G Hkv), the K/V head varying fastest
+  int tile_of_f, g_of_f, h_of_f;
+  auto split = [&](int f) {
+    tile_of_f = fast_div(f, div_heads);
+    const int hp = f - tile_of_f * heads;
+    const int hg = fast_div(hp, div_hkv);
+    g_of_f = hp - hg * Hkv;
+    h_of_f = g_of_f * G + hg;
+  };
+  auto load_rec = [&](int tile) { return recs[(size_t)tile * kRecInts + min(lane, kRecInts - 1)]; };
 
-  stage_k(kbufs, k_cache, block_id(bt_row, kq, nblk_total), head_off, blk_stride, wave, lane);
-  stage_v(vbufs, v_cache, __builtin_amdgcn_readfirstlane(block_id(bt_row, vq, nblk_total)), head_off, blk_stride,
-          wave, lane);
-  // K tile 1 goes out with tile 0 (both K buffers are free), which saves one memory round
-  // trip in the prologue
-  if (n_tiles > 1)
-    stage_k(kbufs + kKTileBytes, k_cache, block_id(bt_row, 4 + kq, nblk_total), head_off, blk_stride, wave, lane);
+  // The first two tickets of every workgroup are fixed (the plan starts the counters behind them):
+  // several hundred workgroups asking eight counters at once would wait on each other.
+  if (tid == 0) {
+    const int iq = blockIdx.x / kQueues;                                   // index in the queue's crew
+    const int nq = ((int)gridDim.x - queue + kQueues - 1) / kQueues;       // size of the crew
+    const int f0 = resolve(iq);
+    slot[0] = f0;
+    slot[1] = f0 >= 0 ? resolve(iq + nq) : -1;
+  }
+  __syncthreads();
+  int f_cur = __builtin_amdgcn_readfirstlane(slot[0]);    // the item being computed
+  int f_next = __builtin_amdgcn_readfirstlane(slot[1]);   // the one after it (-1: none)
+  if (f_cur < 0) return;
+
+  split(f_cur);
+  int rec_next = load_rec(tile_of_f);  // record of the next item (here: of the first)
+  int pend = 0;                        // (thread 0) ticket on its way
+  Item cur = describe(rec_next, g_of_f, h_of_f, block_table, bt_stride);
+  int g_next = 0, h_next = 0;                    // heads of the next item
+
+  // per-lane view of the current item
+  int row, pos, w_pmin, n_w;
+  bool row_valid;
+  size_t head_off;
+  auto enter = [&](const Item& t) {
+    row = t.q0 + wave * 32 + col;                          // this lane's query row inside the sequence
+    row_valid = row < t.S;
+    pos = t.cb + row;                                      // absolute position = causal bound
+    w_pmin = t.cb + t.q0 + wave * 32;                      // smallest / largest bound in this wavefront
+    const int w_pmax = t.cb + min(t.S - 1, t.q0 + wave * 32 + 31);
+    n_w = min(t.n_tiles, w_pmax / kTK + 1);                // steps not wholly above this wavefront's diagonal
+    head_off = (size_t)t.g * 4096;
+  };
+  enter(cur);
 
   // B operand of S^T: Q^T[d][row]; step t covers d = 16 t .. 16 t + 15
   bf16x8 qf[8];
-  {
-    const uint16_t* qrow = q + ((size_t)(tok0 + row) * Hq + h) * 128 + half * 8;
+  auto load_q = [&](const Item& t) {
+    const int r = t.q0 + wave * 32 + col;
+    const uint16_t* qrow = q + ((size_t)(t.tok0 + r) * Hq + t.h) * 128 + half * 8;
+    const bool ok = r < t.S;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int i = 0; i < 8; ++i) {
       bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[t] = row_valid ? *reinterpret_cast<const bf16x8*>(qrow + t * 16) : z;
+      qf[i] = ok ? *reinterpret_cast<const bf16x8*>(qrow + i * 16) : z;
     }
-  }
+  };
+  // key steps 0 and 1 and value step 0 of an item (ids from its record) into the buffers of parity p
+  auto stage_first = [&](const Item& t, int r, int p) {
+    const size_t ho = (size_t)t.g * 4096;
+    stage_k(kbufs + p * kKTileBytes, k_cache, __shfl(r, 8 + kq), ho, blk_stride, wave, lane);
+    stage_v(vbufs + p * kVTileBytes, v_cache, __builtin_amdgcn_readlane(r, 8 + wave), ho, blk_stride, wave, lane);
+    stage_k(kbufs + (p ^ 1) * kKTileBytes, k_cache, __shfl(r, 12 + kq), ho, blk_stride, wave, lane);
+  };
 
   f32x16 o[4];
 #pragma unroll
@@ -266,51 +412,43 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   const int a_k_off = (half * kTK + krow) * 16;            // + (2 t * 64 + 32 sub) * 16
   const int a_v_off = half * kVOctStride + col * 16;       // + 2 u * stride + 32 dt * 16
 
+  stage_first(cur, rec_next, 0);
+  load_q(cur);
+  int next_idk = __shfl(rec_next, 16 + kq);                // K ids run two steps ahead of the scores
+  int next_idv = __shfl(rec_next, 12 + vq);                // V ids one step ahead
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (kTK > L_total) {  // the first tile already runs past the end of the sequence
-    fix_tail(vbufs, L_total, tid);
+  if (kTK > cur.L_total()) {  // the first step already runs past the end of the sequence
+    fix_tail(vbufs, cur.L_total(), tid);
     __syncthreads();
   }
+  int par = 0;  // buffer that holds step 0 of the current item
 
-  // ---- prologue: scores of tile 0 -----------------------------------------------------------
-  int next_idk = block_id(bt_row, 8 + kq, nblk_total);     // K ids run two tiles ahead of the scores
-  int next_idv = block_id(bt_row, 4 + vq, nblk_total);     // V ids one tile ahead
-  f32x16 sa[2], sb[2];  // scores of the current / next tile, roles alternate
-  {
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sa[sub][i] = 0.f;
-    const char* kb = kbufs + a_k_off;
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + (2 * t * kTK + 32 * sub) * 16);
-        sa[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], sa[sub], 0, 0, 0);
-      }
-    m = mask_and_max(sa, 0, half, pos, kTK - 1 > w_pmin);
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  f32x16 sa[2], sb[2];  // scores of the current / next step, roles alternate
 
-  // ---- main loop: iteration j turns the scores of tile j into weights and accumulates
-  // V(j) P(j), while the matrix cores already compute the scores of tile j+1 -----------------
-  // One iteration; `sc` holds the (masked) scores of tile j on entry, `sn` receives those of
-  // tile j+1.  The loop calls it with the two arrays swapped in turn, so no copy is needed.
-  auto iteration = [&](int j, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
-    char* const kcur = kbufs + (j & 1) * kKTileBytes;          // held K(j), consumed: receives K(j+2)
-    const char* const knext = kbufs + ((j + 1) & 1) * kKTileBytes;
-    const char* const vcur = vbufs + (j & 1) * kVTileBytes;
-    char* const vnext = vbufs + ((j + 1) & 1) * kVTileBytes;
-#ifndef ECO_EXPERIMENT_NO_STAGE
-    if (j + 2 < n_tiles) stage_k(kcur, k_cache, next_idk, head_off, blk_stride, wave, lane);
-    if (j + 1 < n_tiles)
+  // One step of an item: turns the scores of step j (`sc`, masked) into weights and accumulates
+  // V(j) P(j) while the matrix cores already compute the scores of step j+1 into `sn`.  The loop
+  // calls it with the two arrays swapped in turn, so no copy is needed.  The last step of an item
+  // has no next scores to compute; instead it brings in the first K/V steps and the query rows
+  // of the next item, so that the only cost of changing items is the unoverlapped score product
+  // of the new item's step 0.
+  auto iteration = [&](auto last_tag, int j, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+    constexpr bool is_last = decltype(last_tag)::value;
+    const int pj = (j + par) & 1;
+    char* const kcur = kbufs + pj * kKTileBytes;               // held K(j), consumed: receives K(j+2)
+    const char* const knext = kbufs + (pj ^ 1) * kKTileBytes;
+    const char* const vcur = vbufs + pj * kVTileBytes;
+    char* const vnext = vbufs + (pj ^ 1) * kVTileBytes;
+    if constexpr (!is_last) {
+      if (j + 2 < cur.n_tiles) stage_k(kcur, k_cache, next_idk, head_off, blk_stride, wave, lane);
       stage_v(vnext, v_cache, __builtin_amdgcn_readfirstlane(next_idv), head_off, blk_stride, wave, lane);
-#endif
-    next_idk = block_id(bt_row, 4 * (j + 3) + kq, nblk_total);
-    next_idv = block_id(bt_row, 4 * (j + 2) + vq, nblk_total);
+      next_idk = block_id(cur.bt_row, 4 * (j + 3) + kq, cur.nblk_total());
+      next_idv = block_id(cur.bt_row, 4 * (j + 2) + vq, cur.nblk_total());
+    } else if (f_next >= 0) {
+      const Item nxt = describe(rec_next, g_next, h_next, block_table, bt_stride);
+      stage_first(nxt, rec_next, pj ^ 1);
+      load_q(nxt);  // the current item's scores are all computed: its query rows make room
+    }
 
     if (j < n_w) {  // uniform per wavefront
       const float mc = m * c;
@@ -319,36 +457,25 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
       bf16x8 pf0[2], pf1[2];
       const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
       float pv[2];
-      // 32 matrix instructions per iteration, in this order:
-      //   slots  0..15  scores of tile j+1: step t = slot/2, 32-key half = slot%2
-      //   slots 16..23  O += V P, keys  0..31 of tile j: d tile = i%4, 16-key step = i/4
+      // 32 matrix instructions per step, in this order:
+      //   slots  0..15  scores of step j+1: d step t = slot/2, 32-key half = slot%2
+      //   slots 16..23  O += V P, keys  0..31 of step j: d tile = i%4, 16-key step = i/4
       //   slots 24..31  O += V P, keys 32..63
       // Consecutive slots write different accumulators (a dependent matrix instruction cannot
       // issue back to back).  Each slot is followed by the slice of softmax VALU work that
       // runs under it (one weight of keys 0..31 per slot in 0..15, two weights of keys 32..63
       // per slot in 16..23), and the LDS read of a slot's A fragment is issued kAhead slots
-      // early.  The fences keep the compiler from regrouping the slots.
+      // early.  The fences keep the compiler from regrouping the slots.  The last step of an
+      // item skips the matrix instructions of slots 0..15.
       constexpr int kAhead = 4;
-      auto frag = [&](int slot) -> bf16x8 {
-#ifdef ECO_EXPERIMENT_NO_LDS
-        return qf[slot & 7];
-#endif
-        if (slot < 16) return *reinterpret_cast<const bf16x8*>(kb + (2 * (slot >> 1) * kTK + 32 * (slot & 1)) * 16);
-        const int i = slot & 7;
-        return *reinterpret_cast<const bf16x8*>(vb + (2 * (i >> 2) + (slot < 24 ? 0 : 4)) * kVOctStride +
+      auto frag = [&](int s) -> bf16x8 {
+        if (s < 16) return *reinterpret_cast<const bf16x8*>(kb + (2 * (s >> 1) * kTK + 32 * (s & 1)) * 16);
+        const int i = s & 7;
+        return *reinterpret_cast<const bf16x8*>(vb + (2 * (i >> 2) + (s < 24 ? 0 : 4)) * kVOctStride +
                                                 (i & 3) * 32 * 16);
       };
       // one weight: value e of accumulator s -> pv[e & 1]; every second one completes a pair
       auto weight = [&](const f32x16& s, bf16x8 (&pf)[2], int e) {
-#ifdef ECO_EXPERIMENT_NO_SOFTMAX
-        pv[e & 1] = s[e];
-        if (e & 1) {
-          const bf16x2 a = {(__bf16)pv[0], (__bf16)pv[1]};
-          pf[e >> 3][(e & 7) - 1] = a[0];
-          pf[e >> 3][(e & 7)] = a[1];
-        }
-        return;
-#endif
         pv[e & 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -mc));
         if (e & 1) {
           const bf16x2 a = {(__bf16)pv[0], (__bf16)pv[1]};
@@ -362,92 +489,169 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
       for (int i = 0; i < 16; ++i) zero[i] = 0.f;
       bf16x8 fr[2 * kAhead];
 #pragma unroll
-      for (int slot = 0; slot < kAhead; ++slot) fr[slot] = frag(slot);
+      for (int s = 0; s < kAhead; ++s) fr[s] = frag(s);
 #pragma unroll
-      for (int slot = 0; slot < 32; ++slot) {
-        if (slot + kAhead < 32) fr[(slot + kAhead) % (2 * kAhead)] = frag(slot + kAhead);
-        const bf16x8 a = fr[slot % (2 * kAhead)];
-        if (slot < 16) {
-          sn[slot & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[slot >> 1], slot < 2 ? zero : sn[slot & 1], 0, 0, 0);
-          weight(sc[0], pf0, slot);
-        } else if (slot < 24) {
-          const int i = slot - 16;
+      for (int s = 0; s < 32; ++s) {
+        if (s + kAhead < 32) fr[(s + kAhead) % (2 * kAhead)] = frag(s + kAhead);
+        const bf16x8 a = fr[s % (2 * kAhead)];
+        if (s < 16) {
+          if constexpr (!is_last)
+            sn[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s >> 1], s < 2 ? zero : sn[s & 1], 0, 0, 0);
+          weight(sc[0], pf0, s);
+        } else if (s < 24) {
+          const int i = s - 16;
           o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf0[i >> 2], o[i & 3], 0, 0, 0);
           weight(sc[1], pf1, 2 * i);
           weight(sc[1], pf1, 2 * i + 1);
         } else {
-          const int i = slot - 24;
+          const int i = s - 24;
           o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf1[i >> 2], o[i & 3], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      const int k0n = (j + 1) * kTK;
-      const float bm = mask_and_max(sn, k0n, half, pos, k0n + kTK - 1 > w_pmin);
-      if (__any((bm - m) * c > kTau)) {
-        // the next tile's scores exceed the exponent offset by more than 2^kTau: raise it
-        const float m_new = fmaxf(m, bm);
-        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-        l *= alpha;
+      if constexpr (!is_last) {
+        const int k0n = (j + 1) * kTK;
+        const float bm = mask_and_max(sn, k0n, half, pos, k0n + kTK - 1 > w_pmin);
+        if (__any((bm - m) * c > kTau)) {
+          // the next step's scores exceed the exponent offset by more than 2^kTau: raise it
+          const float m_new = fmaxf(m, bm);
+          const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+          l *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
-        m = m_new;
+          for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
+          m = m_new;
+        }
       }
     }
 
-#if defined(ECO_EXPERIMENT_NO_BARRIER) && defined(ECO_EXPERIMENT_NO_STAGE)
-    return;
-#endif
-#ifndef ECO_EXPERIMENT_NO_WAIT
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
+    // the ticket requested when this item began has arrived: publish the item it stands for
+    if (j == 0 && tid == 0 && f_next >= 0) slot[0] = resolve(pend);
     __syncthreads();
-    if (j + 1 < n_tiles && (j + 2) * kTK > L_total) {  // the next V tile runs past the end of the sequence
-      fix_tail(vnext, L_total - (j + 1) * kTK, tid);
-      __syncthreads();
+    if constexpr (!is_last) {
+      if ((j + 2) * kTK > cur.L_total()) {  // the next V step runs past the end of the sequence
+        fix_tail(vnext, cur.L_total() - (j + 1) * kTK, tid);
+        __syncthreads();
+      }
+    } else if (f_next >= 0) {
+      const int L_next = __builtin_amdgcn_readlane(rec_next, 3) + __builtin_amdgcn_readlane(rec_next, 4);
+      if (kTK > L_next) {
+        fix_tail(vnext, L_next, tid);
+        __syncthreads();
+      }
     }
   };
-  for (int j = 0; j < n_tiles; j += 2) {
-    iteration(j, sa, sb);
-    if (j + 1 < n_tiles) iteration(j + 1, sb, sa);
-  }
 
-#ifdef ECO_EXPERIMENT_NO_WAIT
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-  {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
-    l = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-  if (row_valid) {
-    const float inv = 1.f / l;
-    uint16_t* orow = out + ((size_t)(tok0 + row) * Hq + h) * 128;
+  for (;;) {
+    // K steps 0 and 1 and V step 0 of the current item are in LDS (step 0 in the buffers of
+    // parity `par`), its query rows in qf.  Ask for the record of the next item and for the
+    // ticket of the one after it; both arrive while this item is being computed.
+    if (f_next >= 0) {
+      split(f_next);
+      g_next = g_of_f;
+      h_next = h_of_f;
+      rec_next = load_rec(tile_of_f);
+      if (tid == 0) pend = atomicAdd(counter, 1);
+    }
+    {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sa[sub][i] = 0.f;
+      const char* kb = kbufs + par * kKTileBytes + a_k_off;
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + (2 * t * kTK + 32 * sub) * 16);
+          sa[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], sa[sub], 0, 0, 0);
+        }
+      m = mask_and_max(sa, 0, half, pos, kTK - 1 > w_pmin);
+    }
+    __syncthreads();  // K step 0 is consumed: its buffer receives step 2
+
+    {
+      // the last step always takes its scores from sa: an odd number of plain steps comes in pairs after one single
+      int j = 0;
+      for (; j + 2 < cur.n_tiles; j += 2) {
+        iteration(std::false_type(), j, sa, sb);
+        iteration(std::false_type(), j + 1, sb, sa);
+      }
+      if (j + 2 == cur.n_tiles) {
+        iteration(std::false_type(), j, sa, sb);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) sa[sub] = sb[sub];
+        ++j;
+      }
+      iteration(std::true_type(), j, sa, sb);
+    }
+
+    {
+      const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
+      l = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    {
+      // Registers 4 i4 .. 4 i4 + 3 of o[dt] hold d = 32 dt + 8 i4 + 4 half + (0..3): 8 bytes of output.
+      // The two lanes of a row exchange halves (one v_permlane32_swap per register pair) so that
+      // the lower lane holds the 16 bytes of d = 32 dt + 16 p .. + 7 and the upper lane the next 16.
+      const float inv = 1.f / l;
+      uint16_t* orow = out + ((size_t)(cur.tok0 + row) * Hq + cur.h) * 128 + half * 8;
+      auto pack = [&](float a, float b) {
+        const bf16x2 v = {(__bf16)(a * inv), (__bf16)(b * inv)};
+        return __builtin_bit_cast(uint32_t, v);
+      };
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          const f32x16& v = o[dt];
+          const auto r0 = __builtin_amdgcn_permlane32_swap(pack(v[8 * p + 0], v[8 * p + 1]),
+                                                           pack(v[8 * p + 4], v[8 * p + 5]), false, false);
+          const auto r1 = __builtin_amdgcn_permlane32_swap(pack(v[8 * p + 2], v[8 * p + 3]),
+                                                           pack(v[8 * p + 6], v[8 * p + 7]), false, false);
+          u32x4 w;
+          w[0] = r0[0];
+          w[1] = r1[0];
+          w[2] = r0[1];
+          w[3] = r1[1];
+          if (row_valid) *reinterpret_cast<u32x4*>(orow + dt * 32 + p * 16) = w;
+        }
+    }
+    if (row_valid) {
+      if (lse && half == 0) lse[(size_t)(cur.tok0 + row) * Hq + cur.h] = (m * c + log2f(l)) * kLn2;
+    }
+    if (f_next < 0) break;
+
+    // next item: its first steps were staged by the last step above, into the other parity
+    par = (par + cur.n_tiles) & 1;
+    cur = describe(rec_next, g_next, h_next, block_table, bt_stride);
+    f_next = __builtin_amdgcn_readfirstlane(slot[0]);
+    enter(cur);
+    next_idk = __shfl(rec_next, 16 + kq);
+    next_idv = __shfl(rec_next, 12 + vq);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        // registers 4*i4 .. 4*i4+3 hold d = 32 dt + 8 i4 + 4 half + (0..3)
-        u32x2 w;
-        w[0] = (uint32_t)float_to_bf16_bits(o[dt][4 * i4 + 0] * inv) |
-               ((uint32_t)float_to_bf16_bits(o[dt][4 * i4 + 1] * inv) << 16);
-        w[1] = (uint32_t)float_to_bf16_bits(o[dt][4 * i4 + 2] * inv) |
-               ((uint32_t)float_to_bf16_bits(o[dt][4 * i4 + 3] * inv) << 16);
-        *reinterpret_cast<u32x2*>(orow + dt * 32 + i4 * 8 + half * 4) = w;
-      }
-    if (lse && half == 0) lse[(size_t)(tok0 + row) * Hq + h] = (m * c + log2f(l)) * kLn2;
+      for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+    l = 0.f;
   }
 }
 
 hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
-                               int32_t /*max_q_len*/, hipStream_t s) {
+                               int32_t /*max_q_len*/, int32_t* ws_plan, int32_t n_persistent_wgs, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   // sum over sequences of ceil(S_b / kTQ) <= T / kTQ + (number of non-empty sequences)
-  const int64_t max_tiles = (int64_t)T / kTQ + (a.B < T ? a.B : T);
-  const int64_t n_wg = max_tiles * G * a.Hkv;
-  if (n_wg <= 0) return hipSuccess;
-  if (n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int64_t max_tiles = prefill_plan_tiles(a.B, T);
+  const int64_t n_items = max_tiles * G * a.Hkv;
+  if (n_items <= 0) return hipSuccess;
+  if (n_items > 0x7fffffffLL - (1 << 20)) return hipErrorInvalidValue;
+  const int64_t n_wg = n_items < n_persistent_wgs ? n_items : n_persistent_wgs;
+  hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, cu_q, ctx_before, a.block_table,
+                     a.bt_stride, a.B, (int)n_wg, ws_plan);
   hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q,
-                     (const char*)a.k_cache, (const char*)a.v_cache, cu_q, ctx_before, a.block_table, a.bt_stride,
-                     (uint16_t*)a.out, a.lse, a.B, a.Hq, a.Hkv, G, a.scale_log2e);
+                     (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
+                     a.lse, ws_plan, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)), make_divisor((uint32_t)a.Hkv),
+                     a.scale_log2e);
   return hipGetLastError();
 }
 

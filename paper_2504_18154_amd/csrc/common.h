@@ -16,12 +16,40 @@ constexpr int kMinSplitTokens = 64;   // smallest decode split
 constexpr int kMaxSplitTokens = 4096; // largest forced decode split
 constexpr int kDecodeWgsPerCu = 1;    // persistent decode grid: workgroups per CU (one wavefront per SIMD)
 constexpr int kMaxBatch = 4096;       // largest max_batch a context accepts (batch prefix sums live in LDS)
+constexpr int kPrefillTileRows = 128; // query rows of one prefill work item
+constexpr int kPrefillWgsPerCu = 2;   // persistent prefill grid: workgroups per CU
+constexpr int kPlanMaxQueues = 8;     // prefill plan: most work queues
+constexpr int kPlanCounter0 = 32;     // prefill plan: first queue counter; each counter has a cache line of its own
+constexpr int kPlanCounterStride = 32;
+constexpr int kPlanHeaderInts = kPlanCounter0 + kPlanCounterStride * kPlanMaxQueues;  // then the records
+constexpr int kRecInts = 20;          // prefill plan: int32 fields per query-tile record
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 struct EventPair {
   hipEvent_t start, stop;
 };
+
+// Division of n < 2^31 by a fixed d >= 1 without a divide: q = (mulhi(n, magic) + n) >> shift with
+// shift = ceil(log2 d), magic = floor(2^(32 + shift) / d) + 1 - 2^32 (round-up method; the sum
+// cannot overflow because n < 2^31 and mulhi(n, magic) <= n).
+struct Divisor {
+  uint32_t magic, shift, d;
+};
+inline Divisor make_divisor(uint32_t d) {
+  Divisor v;
+  v.d = d;
+  v.shift = 0;
+  while ((1u << v.shift) < d) ++v.shift;
+  v.magic = (uint32_t)((((uint64_t)1 << (32 + v.shift)) / d) + 1 - ((uint64_t)1 << 32));
+  return v;
+}
+
+// Upper bound, computable on the host, on the number of query tiles of a prefill batch:
+// sum over sequences of ceil(S_b / 128) <= T / 128 + (number of non-empty sequences).
+inline int64_t prefill_plan_tiles(int32_t B, int32_t T) {
+  return (int64_t)T / kPrefillTileRows + (B < T ? B : T);
+}
 
 }  // namespace eco
 
@@ -41,6 +69,8 @@ struct ecoserve_ctx {
   float* ws_ml;                // [max_batch][Hq][ws_splits][2]
   int32_t* ws_meta;            // [max_batch + 3]: chunk size and batch prefix sums of the last decode launch
   int32_t ws_splits;
+  int32_t* ws_plan;            // prefill plan: header and one record per query tile of the last prefill launch
+  int64_t plan_tiles;          // records ws_plan has room for
   size_t ws_bytes;
   // profiling
   std::vector<eco::EventPair> ev[3];
@@ -88,8 +118,9 @@ hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, cons
                                     const int32_t* ws_meta, int32_t ws_splits, hipStream_t s);
 
 // attn_prefill_mfma.hip: bf16, D = 128
+// (ws_plan must hold kPlanHeaderInts + prefill_plan_tiles(B, T) * kRecInts int32)
 hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
-                               int32_t max_q_len, hipStream_t s);
+                               int32_t max_q_len, int32_t* ws_plan, int32_t n_persistent_wgs, hipStream_t s);
 
 }  // namespace eco
 
@@ -103,6 +134,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ int fast_div(int n, const Divisor& v) {
+  return (int)((__umulhi((uint32_t)n, v.magic) + (uint32_t)n) >> v.shift);
+}
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
