@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalid as a result)")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split size (tuning)")
+    ap.add_argument("--equal-shares", action="store_true",
+                    help="decode with equal chunks per wavefront instead of per-XCD shares that follow measured speeds")
     ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
                     help="run only one phase (profiling runs; the default is the full step)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -86,6 +88,8 @@ def main() -> int:
     dctx = binding.Context(model.Hq, model.Hkv, model.D, db.num_blocks, "bf16", db.B, db.block_table.shape[1])
     if args.split_tokens:
         dctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, args.split_tokens)
+    if not args.equal_shares:
+        dctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
     pool_elems = db.num_blocks * model.Hkv * model.bs * model.D
     d_bt, d_len = i32(db.block_table), i32(db.ctx_len)
     d_before = i32(db.ctx_len - 1)
@@ -191,7 +195,7 @@ def main() -> int:
             "workload": "30B-scale PaDG step: prefill-only batch (16 prompts, lognormal mean 1024 in [128,4096]) "
                         "then decode-only batch (128 seqs, ctx U[512,4096]); 40 q heads / 8 kv heads / D 128 / "
                         "block 16; append + attention per layer",
-            "layers": layers, "phase": args.phase,
+            "layers": layers, "phase": args.phase, "decode_shares": "equal" if args.equal_shares else "per-XCD, measured",
             "decode_batch": db.B, "decode_ctx_tokens": int(db.ctx_len.sum()),
             "prefill_prompts": pb.B, "prefill_tokens": pb.T, "prefill_lengths": [int(x) for x in pb.q_len],
         },

@@ -94,7 +94,14 @@ enum {
   ECOSERVE_OPT_FORCE_PLAIN = 2,
   /* 1: bracket the dominant kernel of each hot call with HIP events on the
    * call's stream; read the sums with ecoserve_profile_read(). */
-  ECOSERVE_OPT_PROFILE = 3
+  ECOSERVE_OPT_PROFILE = 3,
+  /* 1: decode (bf16, head size 128, built-in split) cuts the K/V stream into per-XCD shares that
+   * follow the speeds measured in the context's earlier decode calls (the XCDs of one device
+   * differ by several percent and finish together only with unequal shares).  Results stay
+   * within the tolerance of the split-context merge but are no longer bit-identical from call
+   * to call, because the cut points move with the measurements.  0 (default): equal shares,
+   * bit-reproducible. */
+  ECOSERVE_OPT_DECODE_ADAPTIVE = 4
 };
 
 enum { ECOSERVE_KERNEL_APPEND = 0, ECOSERVE_KERNEL_PREFILL = 1, ECOSERVE_KERNEL_DECODE = 2 };

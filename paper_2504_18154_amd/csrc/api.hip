@@ -69,7 +69,7 @@ int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
   const size_t ml_bytes = slots * 2 * sizeof(float);
   if (slots == 0) return ECOSERVE_OK;
   if (hipMalloc(&c->ws_acc, acc_bytes) != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_ENOMEM; }
-  const size_t meta_bytes = ((size_t)c->max_batch + 3) * sizeof(int32_t);
+  const size_t meta_bytes = ((size_t)c->max_batch + 19) * sizeof(int32_t);
   // a prefill batch cannot bring more new tokens than the pool holds
   c->plan_tiles = prefill_plan_tiles(c->max_batch, (int32_t)std::min<int64_t>(
                                                         (int64_t)c->lay.num_blocks * kBlockSize, 0x7fffffffLL));
@@ -188,6 +188,9 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   c->opt_split_tokens = 0;
   c->opt_force_plain = 0;
   c->opt_profile = 0;
+  c->opt_adaptive = 0;
+  c->share_parity = 0;
+  c->ws_share = nullptr;
   c->ws_acc = nullptr;
   c->ws_ml = nullptr;
   c->ws_meta = nullptr;
@@ -198,6 +201,18 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   for (int i = 0; i < 3; ++i) c->ev_used[i] = 0;
   st = alloc_workspace(c, kMinSplitTokens);
   if (st != ECOSERVE_OK) { delete c; return st; }
+  {
+    // per-XCD shares start equal; samples of 4 wavefronts per CU follow
+    const size_t share_bytes = (24 + 2 * (size_t)c->num_cu * kDecodeWgsPerCu * 4) * sizeof(int32_t);
+    const float ones[16] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+    if (hipMalloc(&c->ws_share, share_bytes) != hipSuccess || hipMemset(c->ws_share, 0, share_bytes) != hipSuccess ||
+        hipMemcpy(c->ws_share, ones, sizeof(ones), hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)ecoserve_destroy(c);
+      return ECOSERVE_ENOMEM;
+    }
+    c->ws_bytes += share_bytes;
+  }
   *out = c;
   return ECOSERVE_OK;
 }
@@ -211,6 +226,7 @@ int ecoserve_destroy(ecoserve_ctx* c) {
   if (c->ws_ml) (void)hipFree(c->ws_ml);
   if (c->ws_meta) (void)hipFree(c->ws_meta);
   if (c->ws_plan) (void)hipFree(c->ws_plan);
+  if (c->ws_share) (void)hipFree(c->ws_share);
   for (int i = 0; i < 3; ++i)
     for (EventPair& e : c->ev[i]) { (void)hipEventDestroy(e.start); (void)hipEventDestroy(e.stop); }
   delete c;
@@ -229,6 +245,9 @@ int ecoserve_set_option(ecoserve_ctx* c, int32_t option, int32_t value) {
       return ECOSERVE_OK;
     case ECOSERVE_OPT_PROFILE:
       c->opt_profile = value ? 1 : 0;
+      return ECOSERVE_OK;
+    case ECOSERVE_OPT_DECODE_ADAPTIVE:
+      c->opt_adaptive = value ? 1 : 0;
       return ECOSERVE_OK;
     default:
       return ECOSERVE_EINVAL;
@@ -313,15 +332,20 @@ int ecoserve_attn_decode(ecoserve_ctx* c, const void* q, const void* k_cache, co
   const AttnArgs a = make_args(c, q, k_cache, v_cache, block_table, bt_stride, out, lse, B);
   hipError_t e;
   if (use_mfma(c)) {
+    const int n_wgs = c->num_cu * kDecodeWgsPerCu;
+    const bool adaptive = c->opt_adaptive && c->opt_split_tokens == 0 && n_wgs % 8 == 0;
+    const float* const share_in = adaptive ? c->ws_share + 8 * c->share_parity : nullptr;
+    float* const share_out = adaptive ? c->ws_share + 8 * (1 - c->share_parity) : nullptr;
+    float* const speed = adaptive ? c->ws_share + 16 : nullptr;
+    int32_t* const wave_samples = adaptive ? reinterpret_cast<int32_t*>(c->ws_share + 24) : nullptr;
+    if (adaptive) c->share_parity ^= 1;
     {
       ProfileScope prof(c, ECOSERVE_KERNEL_DECODE, s);
-      e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len,
-                             c->num_cu * kDecodeWgsPerCu,
-                             c->ws_acc, c->ws_ml, c->ws_meta,
-                             c->ws_splits, s);
+      e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len, n_wgs, c->ws_acc, c->ws_ml, c->ws_meta,
+                             c->ws_splits, share_in, share_out, speed, wave_samples, s);
     }
     if (e != hipSuccess) return ECOSERVE_EHIP;
-    e = launch_decode_mfma_merge(a, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, s);
+    e = launch_decode_mfma_merge(a, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, speed, wave_samples, n_wgs * 4, s);
     return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
   }
   const int32_t split_tokens = plan_split_tokens(c, B, max_ctx_len);

@@ -15,7 +15,11 @@
 // integers).  All wavefronts therefore stream the same number of bytes whatever the mix of
 // context lengths, start together and finish together.  A chunk may cover the tail of one
 // (sequence, head), several whole ones and the head of another; each covered piece yields
-// one partial softmax state.
+// one partial softmax state.  On request the chunks are not equal but proportional to the
+// speed of the XCD a wavefront runs on, as measured by the context's earlier launches (the
+// XCDs of one device stream at rates several percent apart, stable over time): every
+// wavefront records units and time, the merge kernel turns them into per-XCD shares for
+// the next launch.
 //
 // Per piece, the wavefront streams whole cache blocks with fully coalesced per-lane loads
 // that land directly in MFMA operand layout - no LDS staging, no barriers, a register
@@ -137,31 +141,102 @@ __device__ __forceinline__ long long chunk_units(long long U, int n_waves, int c
   return c < kMinSplitTokens / kBlockSize ? kMinSplitTokens / kBlockSize : c;
 }
 
+// The numbering of units is dealt to the wavefronts in rounds of 8 workgroups (workgroup ids go
+// round-robin to the 8 XCDs, so position x of a round runs on XCD x): the 4 wavefronts of the
+// workgroup at position x take c[x] units each, cum[x] = 4 (c[0] + .. + c[x-1]) units into the
+// round, cum[8] units per round.  With equal c this is plain "wavefront w takes units
+// [w c, (w + 1) c)"; unequal c let the XCDs carry shares of the stream in proportion to their
+// measured speeds.
+struct Chunking {
+  const int* c;    // [8]
+  const int* cum;  // [9]
+  __device__ __forceinline__ long long begin(int gw) const {
+    const int wg = gw >> 2, x = wg & 7;
+    return (long long)(wg >> 3) * cum[8] + cum[x] + (gw & 3) * c[x];
+  }
+  __device__ __forceinline__ int size(int gw) const { return c[(gw >> 2) & 7]; }
+  __device__ __forceinline__ int owner(long long u) const {  // the wavefront whose chunk holds unit u
+    const long long r = u / cum[8];
+    const int off = (int)(u - r * cum[8]);
+    int x = 0;
+#pragma unroll
+    for (int y = 1; y < 8; ++y)
+      if (cum[y] <= off) x = y;
+    return (int)((r * 8 + x) * 4 + (off - cum[x]) / c[x]);
+  }
+};
+constexpr int kMetaPre = 18;  // ws_meta: [0..7] c, [8..16] cum, then the batch prefix sums
+
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
-    int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, int B, int Hq, int Hkv, int G, float scale_log2e) {
+    int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, const float* __restrict__ share_in,
+    float* __restrict__ share_out, const float* __restrict__ xcd_speed, int32_t* __restrict__ ws_wave, int B, int Hq,
+    int Hkv, int G, float scale_log2e) {
   __shared__ int pre[kMaxBatch + 1];
   __shared__ int lens[kMaxBatch];
   __shared__ int wsum[kWaves];
+  __shared__ int s_c[8], s_cum[9];
+  const long long t_start = wall_clock64();
   scan_block_counts(pre, lens, wsum, ctx_len, B);
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, quad = lane >> 4;
   const int n_waves = gridDim.x * kWaves;
   const long long U = (long long)pre[B] * Hkv;
-  const long long C = chunk_units(U, n_waves, c_forced);
+  if (threadIdx.x == 0) {
+    const long long C = chunk_units(U, n_waves, c_forced);
+    // Per-XCD chunk sizes from the shares (mean 1); equal chunks if there are none, or if
+    // rounding left the rounds short of covering all units.  The shares move half way from
+    // their previous values towards the relative speeds that the previous launch measured
+    // (every workgroup computes the same numbers; the first one stores them for the next launch).
+    int c[8];
+    long long sum = 0;
+    if (share_in) {
+      float share[8], mean = 0.f, total = 0.f;
+      bool measured = true;
+      for (int x = 0; x < 8; ++x) {
+        share[x] = share_in[x];
+        mean += xcd_speed[x];
+        measured = measured && xcd_speed[x] > 0.f;
+      }
+      mean *= 0.125f;
+      if (measured)
+        for (int x = 0; x < 8; ++x) share[x] = fminf(1.5f, fmaxf(0.5f, 0.5f * share[x] + 0.5f * xcd_speed[x] / mean));
+      for (int x = 0; x < 8; ++x) total += share[x];
+      for (int x = 0; x < 8; ++x) {
+        share[x] *= 8.f / total;
+        if (blockIdx.x == 0) share_out[x] = share[x];
+        c[x] = max(kMinSplitTokens / kBlockSize, (int)(share[x] * ((float)U / (float)n_waves)) + 1);
+        sum += c[x];
+      }
+    }
+    const bool ok = share_in && 4 * sum * (gridDim.x >> 3) >= U;
+    int cum = 0;
+    for (int x = 0; x < 8; ++x) {
+      s_c[x] = ok ? c[x] : (int)C;
+      s_cum[x] = cum;
+      cum += 4 * s_c[x];
+    }
+    s_cum[8] = cum;
+  }
+  __syncthreads();
+  const Chunking ch = {s_c, s_cum};
   if (blockIdx.x == 0) {
     // the merge kernel reads the numbering instead of recomputing it
-    for (int i = threadIdx.x; i <= B; i += kWaves * 64) ws_meta[2 + i] = pre[i];
-    if (threadIdx.x == 0) ws_meta[0] = (int)C;
+    for (int i = threadIdx.x; i <= B; i += kWaves * 64) ws_meta[kMetaPre + i] = pre[i];
+    if (threadIdx.x < 8) ws_meta[threadIdx.x] = s_c[threadIdx.x];
+    if (threadIdx.x < 9) ws_meta[8 + threadIdx.x] = s_cum[threadIdx.x];
   }
   const int gw = blockIdx.x * kWaves + wave;
-  const long long u_begin = (long long)gw * C;
-  const long long u_end = min(U, u_begin + C);
+  const long long u_begin = ch.begin(gw);
+  const long long u_end = min(U, u_begin + ch.size(gw));
   const size_t blk_stride = (size_t)Hkv * 4096;
-  if (u_begin >= u_end) return;
+  if (u_begin >= u_end) {
+    if (ws_wave && lane == 0) ws_wave[2 * gw] = 0;  // no units: not a sample of this XCD's speed
+    return;
+  }
 
   // A piece: the blocks [blk0, blk0 + n) of one (sequence b, K/V head g) that fall into this
   // wavefront's chunk.  Everything a piece needs before its first K/V load - where it is
@@ -276,7 +351,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
         }
         if (lse && quad == 0) lse[(size_t)cur.b * Hq + h] = (m + log2f(l)) * kLn2;
       } else {
-        const int split = gw - (int)(cur.seg_u0 / C);
+        const int split = gw - ch.owner(cur.seg_u0);
         const size_t slot = ((size_t)cur.b * Hq + h) * ws_splits + split;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
@@ -293,6 +368,32 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     for (int kk = 0; kk < 4; ++kk) qf[kk] = qn[kk];
     ids = ids_n;
   }
+  if (ws_wave && lane == 0) {  // units streamed and time taken (100 MHz ticks), for the XCD shares
+    ws_wave[2 * gw] = (int)(u_end - u_begin);
+    ws_wave[2 * gw + 1] = (int)(wall_clock64() - t_start);
+  }
+}
+
+// Feedback for the next launch: the speed of XCD x is the mean over its wavefronts of units
+// streamed per tick (0 if most of them had nothing to stream: then the launch is too small to
+// tell).  One wavefront per XCD.
+__device__ __forceinline__ void measure_xcd_speed(float* __restrict__ xcd_speed, const int32_t* __restrict__ ws_wave,
+                                                  int n_waves, int x) {
+  float v = 0.f, n = 0.f, idle = 0.f;
+  for (int i = threadIdx.x; 32 * (i >> 2) + 4 * x + (i & 3) < n_waves; i += 64) {
+    const int w = 32 * (i >> 2) + 4 * x + (i & 3);  // wavefront i of XCD x
+    const int units = ws_wave[2 * w], ticks = ws_wave[2 * w + 1];
+    if (units > 0 && ticks > 0) {
+      v += (float)units / (float)ticks;
+      n += 1.f;
+    } else {
+      idle += 1.f;
+    }
+  }
+  v = wave_sum(v);
+  n = wave_sum(n);
+  idle = wave_sum(idle);
+  if (threadIdx.x == 0) xcd_speed[x] = n > idle ? v / n : 0.f;
 }
 
 // Merge of the partial softmax states of every (sequence, query head) that was cut:
@@ -302,12 +403,15 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
                                                               const float* __restrict__ ws_ml,
                                                               const int32_t* __restrict__ ws_meta, int ws_splits,
                                                               uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                              float* __restrict__ xcd_speed,
+                                                              const int32_t* __restrict__ ws_wave, int n_waves,
                                                               int Hq, int Hkv, int G) {
   const int h = blockIdx.x, b = blockIdx.y, g = h / G;
-  const long long C = ws_meta[0];
-  const int p0 = ws_meta[2 + b], nb = ws_meta[2 + b + 1] - p0;
+  if (xcd_speed && b * Hq + h < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, b * Hq + h);
+  const Chunking ch = {ws_meta, ws_meta + 8};
+  const int p0 = ws_meta[kMetaPre + b], nb = ws_meta[kMetaPre + b + 1] - p0;
   const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nb;
-  const int n_split = (int)((seg_u0 + nb - 1) / C - seg_u0 / C) + 1;
+  const int n_split = ch.owner(seg_u0 + nb - 1) - ch.owner(seg_u0) + 1;
   if (n_split <= 1) return;  // written in final form by the decode kernel
   const size_t base = ((size_t)b * Hq + h) * ws_splits;
   const int lane = threadIdx.x;
@@ -329,7 +433,8 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
 
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta,
-                              int32_t ws_splits, hipStream_t s) {
+                              int32_t ws_splits, const float* share_in, float* share_out, const float* xcd_speed,
+                              int32_t* ws_wave, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   int n_wg = n_persistent_wgs;
   int c_forced = 0;
@@ -339,18 +444,23 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
     const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize);
     const long long waves = (u_max + c_forced - 1) / c_forced;
     n_wg = (int)((waves + kWaves - 1) / kWaves);
+    share_in = nullptr;
   }
+  if (n_wg % 8 != 0) share_in = nullptr;  // the rounds of 8 workgroups would not line up with the XCDs
+  if (!share_in) ws_wave = nullptr;
   hipLaunchKernelGGL(decode_mfma_kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q,
                      (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
-                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, a.B, a.Hq, a.Hkv, G,
-                     a.scale_log2e);
+                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out, xcd_speed, ws_wave, a.B, a.Hq,
+                     a.Hkv, G, a.scale_log2e);
   return hipGetLastError();
 }
 
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
-                                    const int32_t* ws_meta, int32_t ws_splits, hipStream_t s) {
+                                    const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
+                                    const int32_t* ws_wave, int32_t n_waves, hipStream_t s) {
   hipLaunchKernelGGL(decode_flat_merge_kernel, dim3((unsigned)a.Hq, (unsigned)a.B), dim3(64), 0, s, ws_acc, ws_ml,
-                     ws_meta, ws_splits, (uint16_t*)a.out, a.lse, a.Hq, a.Hkv, a.Hq / a.Hkv);
+                     ws_meta, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq, a.Hkv,
+                     a.Hq / a.Hkv);
   return hipGetLastError();
 }
 

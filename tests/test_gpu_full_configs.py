@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from oracle import oracle as orc
-from paper_2504_18154_amd import workloads as wl
+from paper_2504_18154_amd import binding, workloads as wl
 from tests.parity_util import Layer, compare, compare_lse, say
 
 pytestmark = pytest.mark.gpu
@@ -48,6 +48,13 @@ def _decode_full(db: wl.DecodeBatch, name):
     compare_lse(f"{name} decode", lse, ref_lse, "bf16")
     out2, _ = layer.decode_gpu(q, db.block_table, db.ctx_len)
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "not run-to-run deterministic"
+    # the configuration bench.py times: per-XCD shares that follow the measured speeds.  The cut
+    # points move from call to call, so every call is held to the oracle, not to the one before.
+    layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
+    for call in range(6):
+        out, lse = layer.decode_gpu(q, db.block_table, db.ctx_len)
+        compare(f"{name} decode, adaptive shares, call {call}", out, ref, "bf16")
+        compare_lse(f"{name} decode, adaptive shares, call {call}", lse, ref_lse, "bf16")
     layer.close()
 
 
