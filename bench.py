@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalid as a result)")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split size (tuning)")
+    ap.add_argument("--prefill-chunk", type=int, default=0,
+                    help="process every prompt in chunks of this many tokens (each chunk attends to the cached prefix "
+                         "of its prompt): quantifies the repeated K/V reads of chunked prefill; 0 = whole prompts")
     ap.add_argument("--equal-shares", action="store_true",
                     help="decode with equal chunks per wavefront instead of per-XCD shares that follow measured speeds")
     ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
@@ -130,6 +133,18 @@ def main() -> int:
     p_k = wl.randn((pb.T, model.Hkv, model.D), "bf16", pb.seed + 4, device=dev)
     p_v = wl.randn((pb.T, model.Hkv, model.D), "bf16", pb.seed + 5, device=dev)
     p_out = torch.empty_like(p_q)
+    # chunked prefill: chunk ci holds tokens [ci C, ci C + C) of every prompt that is that long
+    p_chunks = []
+    if args.prefill_chunk > 0:
+        C = args.prefill_chunk
+        for ci in range((pb.max_q_len + C - 1) // C):
+            lens = np.clip(pb.q_len.astype(np.int64) - ci * C, 0, C)
+            idx = np.concatenate([np.arange(pb.cu_q[b] + ci * C, pb.cu_q[b] + ci * C + lens[b]) for b in range(pb.B)])
+            sel = torch.as_tensor(idx, device=dev, dtype=torch.long)
+            before = np.minimum(pb.q_len, ci * C) + pb.ctx_before
+            p_chunks.append(dict(q=p_q[sel].contiguous(), k=p_k[sel].contiguous(), v=p_v[sel].contiguous(),
+                                 out=torch.empty((len(idx), model.Hq, model.D), dtype=torch.bfloat16, device=dev),
+                                 cu=i32(wl.cu_from_lengths(lens)), before=i32(before), max_len=int(lens.max())))
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -139,8 +154,12 @@ def main() -> int:
         if do_pre:
             for l in range(layers):
                 kc, vc = p_pools[l]
-                pctx.kv_append(kc, vc, p_k, p_v, p_cu, p_before, p_bt, max_new_len=pb.max_q_len)
-                pctx.attn_prefill(p_q, kc, vc, p_cu, p_before, p_bt, p_out, max_q_len=pb.max_q_len)
+                if not p_chunks:
+                    pctx.kv_append(kc, vc, p_k, p_v, p_cu, p_before, p_bt, max_new_len=pb.max_q_len)
+                    pctx.attn_prefill(p_q, kc, vc, p_cu, p_before, p_bt, p_out, max_q_len=pb.max_q_len)
+                for ch in p_chunks:
+                    pctx.kv_append(kc, vc, ch["k"], ch["v"], ch["cu"], ch["before"], p_bt, max_new_len=ch["max_len"])
+                    pctx.attn_prefill(ch["q"], kc, vc, ch["cu"], ch["before"], p_bt, ch["out"], max_q_len=ch["max_len"])
         t[1].record()
         if do_dec:
             for l in range(layers):
@@ -226,18 +245,20 @@ def main() -> int:
                            "algorithmic_bytes_per_launch": dec_bytes_layer}
     if do_pre:
         tf = rate(pre_flops_layer * layers, pre_ms) / 1e12
-        avg_ms = k_pre_ms / max(k_pre_n, 1)
+        calls = max(1, len(p_chunks))  # hot calls per layer (chunked prefill: one per chunk)
+        avg_ms = calls * k_pre_ms / max(k_pre_n, 1)      # kernel time per layer
         ktf = rate(pre_flops_layer, avg_ms) / 1e12
-        app_ms = k_papp_ms / max(k_papp_n, 1)
+        app_ms = calls * k_papp_ms / max(k_papp_n, 1)
         res["prefill"] = {
             "value": tf, "unit": "TFLOP/s", "ms_per_layer": pre_ms / layers, "phase_ms": pre_ms,
             "frac_of_bf16_peak": tf / acc.PEAK_BF16_TFLOPS,
             "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": ktf,
                          "peak": acc.PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ktf / acc.PEAK_BF16_TFLOPS,
-                         "traffic": measured_traffic("prefill_mfma_kernel") if layers == model.layers else None,
-                         "avg_launch_us": avg_ms * 1e3, "launches": k_pre_n,
+                         "traffic": measured_traffic("prefill_mfma_kernel") if layers == model.layers and calls == 1 else None,
+                         "avg_launch_us": avg_ms * 1e3 / calls, "launches": k_pre_n,
                          "algorithmic_flops_per_launch": pre_flops_layer},
-            "append": {"GBps": rate(pre_app_bytes_layer, app_ms) / 1e9, "avg_launch_us": app_ms * 1e3,
+            "chunk_tokens": args.prefill_chunk, "calls_per_layer": calls,
+            "append": {"GBps": rate(pre_app_bytes_layer, app_ms) / 1e9, "avg_launch_us": app_ms * 1e3 / calls,
                        "frac_of_hbm_peak": rate(pre_app_bytes_layer, app_ms) / 1e9 / acc.PEAK_HBM_GBPS},
         }
         if not do_dec:

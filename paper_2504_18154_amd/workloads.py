@@ -52,6 +52,8 @@ class ModelShape:
 TINY = ModelShape("tiny-fp32", Hq=4, Hkv=2, D=64, layers=1, dtype="f32")
 M30B = ModelShape("30B-scale", Hq=40, Hkv=8, D=128, layers=64, dtype="bf16")
 M70B = ModelShape("70B-scale", Hq=64, Hkv=8, D=128, layers=80, dtype="bf16")
+# multi-head attention, no K/V sharing: the head shape of the third model of the paper's evaluation (Section 5.1)
+M30B_MHA = ModelShape("30B-scale-MHA", Hq=52, Hkv=52, D=128, layers=60, dtype="bf16")
 
 
 def config_seed(config_id: int) -> int:

@@ -122,6 +122,58 @@ def test_bf16_decode_split_plans(model):
     layer.close()
 
 
+def test_bf16_multi_head_attention_no_kv_sharing():
+    """52 query heads with a K/V head each (G = 1): the head shape of the multi-head model of the
+    paper's evaluation (Section 5.1).  Prefill over ragged prompts, then decode steps on the grown
+    contexts; decode arithmetic intensity is 1, the purest memory-bound case."""
+    model = wl.ModelShape("mha", 52, 52, 128, 1, "bf16")
+    q_len = [5, 130, 16, 257, 64, 1, 700]
+    say(f"bf16 MHA (G = 1) prefill {q_len} then decode")
+    pb, layer = _mk(model, q_len, seed=21, grow=3)
+    q, k, v = _qkv(model, pb.T, 210)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    compare("MHA prefill", out, ref, "bf16")
+    compare_lse("MHA prefill", lse, ref_lse, "bf16")
+    ctx = pb.q_len.copy()
+    ones = wl.cu_from_lengths([1] * pb.B)
+    for step in range(3):
+        q, k, v = _qkv(model, pb.B, 220 + 10 * step)
+        layer.append(k, v, ones, ctx, pb.block_table, max_new_len=1)
+        ctx = ctx + 1
+        out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+        compare(f"MHA decode step {step}", out, ref, "bf16")
+        compare_lse(f"MHA decode step {step}", lse, ref_lse, "bf16")
+    layer.assert_cache_bit_exact()
+    layer.close()
+
+
+def test_bf16_decode_adaptive_shares_small_and_ragged():
+    """Per-XCD shares on launches that are too small to measure (shares must stay equal and
+    results identical to the equal-share mode) and on ragged contexts over many calls."""
+    from paper_2504_18154_amd import binding
+    model = M30
+    say("bf16 decode with per-XCD shares, ragged contexts")
+    pb, layer = _mk(model, DECODE_LENS + [4000, 3500, 2222, 1234] * 6, seed=23)
+    _, k, v = _qkv(model, pb.T, 230)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    q = wl.randn((pb.B, model.Hq, model.D), "bf16", 231)
+    ref, ref_lse = layer.decode_oracle(q, pb.block_table, pb.q_len)
+    base, _ = layer.decode_gpu(q, pb.block_table, pb.q_len)
+    layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
+    for call in range(20):
+        out, lse = layer.decode_gpu(q, pb.block_table, pb.q_len)
+        compare(f"adaptive call {call}", out, ref, "bf16")
+        compare_lse(f"adaptive call {call}", lse, ref_lse, "bf16")
+    layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 0)
+    again, _ = layer.decode_gpu(q, pb.block_table, pb.q_len)
+    assert torch.equal(base.view(torch.int16), again.view(torch.int16)), "equal-share mode is not reproducible"
+    layer.close()
+
+
 def test_bf16_decode_after_growth_steps():
     """Decode-only phase: several steps, each appending one token per sequence (crossing
     block boundaries) before attending."""
