@@ -174,6 +174,88 @@ def test_bf16_decode_adaptive_shares_small_and_ragged():
     layer.close()
 
 
+@pytest.mark.parametrize("hq,hkv", [(2, 1), (16, 1), (3, 3), (24, 6)], ids=["G2x1", "G16x1", "G1x3", "G4x6"])
+def test_bf16_unusual_head_counts(hq, hkv):
+    """Head counts that are not multiples of the XCD count, the largest supported group (16 query
+    heads per K/V head) and a single K/V head: prefill (with a cached prefix on some sequences)
+    and decode on the matrix-core path."""
+    model = wl.ModelShape(f"h{hq}x{hkv}", hq, hkv, 128, 1, "bf16")
+    first, second = [0, 40, 129, 0, 700, 16], [300, 1, 64, 65, 131, 500]
+    say(f"bf16 {hq} query / {hkv} K/V heads: prefix {first} + new {second}")
+    pb, layer = _mk(model, [a + b for a, b in zip(first, second)], seed=31, grow=2)
+    cu1, cu2 = wl.cu_from_lengths(first), wl.cu_from_lengths(second)
+    cb = np.asarray(first, dtype=np.int32)
+    _, k1, v1 = _qkv(model, int(cu1[-1]), 310)
+    layer.append(k1, v1, cu1, np.zeros(len(first), np.int32), pb.block_table)
+    q2, k2, v2 = _qkv(model, int(cu2[-1]), 320)
+    layer.append(k2, v2, cu2, cb, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q2, cu2, cb, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q2, cu2, cb, pb.block_table)
+    compare("prefill", out, ref, "bf16")
+    compare_lse("prefill", lse, ref_lse, "bf16")
+    ctx = pb.q_len.copy()
+    ones = wl.cu_from_lengths([1] * pb.B)
+    for step in range(2):
+        q, k, v = _qkv(model, pb.B, 330 + 10 * step)
+        layer.append(k, v, ones, ctx, pb.block_table, max_new_len=1)
+        ctx = ctx + 1
+        out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+        compare(f"decode step {step}", out, ref, "bf16")
+        compare_lse(f"decode step {step}", lse, ref_lse, "bf16")
+    layer.close()
+
+
+def test_bf16_large_batch_of_short_sequences():
+    """1500 sequences of 0..70 tokens (the batch prefix sums take more than one entry per thread,
+    most work items are a single key step, many sequences are empty in the prefill call), then a
+    decode step over all of them."""
+    model = wl.ModelShape("small-heads", 8, 2, 128, 1, "bf16")
+    rng = np.random.default_rng(41)
+    q_len = rng.integers(0, 71, size=1500)
+    q_len[[0, 7, 1499]] = [0, 70, 0]
+    say(f"bf16 batch of {len(q_len)} short sequences, {int(q_len.sum())} tokens")
+    pb, layer = _mk(model, q_len, seed=42, grow=1)
+    q, k, v = _qkv(model, pb.T, 410)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    compare("prefill", out, ref, "bf16")
+    compare_lse("prefill", lse, ref_lse, "bf16")
+    ctx = pb.q_len + 1
+    q, k, v = _qkv(model, pb.B, 420)
+    layer.append(k, v, wl.cu_from_lengths([1] * pb.B), pb.q_len, pb.block_table, max_new_len=1)
+    out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+    ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+    compare("decode", out, ref, "bf16")
+    compare_lse("decode", lse, ref_lse, "bf16")
+    layer.assert_cache_bit_exact()
+    layer.close()
+
+
+def test_bf16_short_chunk_after_long_prefix():
+    """A few new tokens behind thousands of cached ones (one query tile, many key steps) next to a
+    long new prompt: the work items differ by two orders of magnitude."""
+    model = M30
+    first, second = [3001, 0, 4090, 777], [5, 1200, 3, 64]
+    say(f"bf16 prefill: prefix {first} + new {second}")
+    pb, layer = _mk(model, [a + b for a, b in zip(first, second)], seed=51)
+    cu1, cu2 = wl.cu_from_lengths(first), wl.cu_from_lengths(second)
+    cb = np.asarray(first, dtype=np.int32)
+    _, k1, v1 = _qkv(model, int(cu1[-1]), 510)
+    layer.append(k1, v1, cu1, np.zeros(4, np.int32), pb.block_table)
+    q2, k2, v2 = _qkv(model, int(cu2[-1]), 520)
+    layer.append(k2, v2, cu2, cb, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q2, cu2, cb, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q2, cu2, cb, pb.block_table)
+    compare("prefill", out, ref, "bf16")
+    compare_lse("prefill", lse, ref_lse, "bf16")
+    layer.close()
+
+
 def test_bf16_decode_after_growth_steps():
     """Decode-only phase: several steps, each appending one token per sequence (crossing
     block boundaries) before attending."""
