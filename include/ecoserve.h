@@ -27,7 +27,8 @@
  *     behaviour.  ecoserve_debug_validate() checks them synchronously.
  *   - One call handles one layer; callers loop over layers.
  *   - Calls that share a context must be issued on one stream (or be ordered
- *     by the caller): they share the context's split-context workspace.
+ *     by the caller): they share the context's workspace (split-context partial
+ *     states of decode, the query-tile list of prefill).
  *
  * Notation (Table 1 of the paper, extended): B sequences in the batch, Hq
  * query heads (M in the paper), Hkv key/value heads, G = Hq/Hkv, D per-head
@@ -164,6 +165,9 @@ int ecoserve_kv_append(ecoserve_ctx* ctx, void* k_cache, void* v_cache, const vo
  *   lse         : dev, float[T][Hq] natural-log sum-exp of the scaled scores, or NULL
  *   max_q_len   : upper bound on any sequence's new-token count (sizes the launch)
  *   Sequences with zero new tokens are skipped.  B == 0 or T == 0 is a no-op.
+ *   T / 128 + min(B, T) must not exceed num_blocks / 8 + max_batch (a batch cannot bring more
+ *   new tokens than the pool holds; the context's list of query tiles is sized for that), else
+ *   ECOSERVE_EINVAL.  The list lives in the context's workspace: see the rule on sharing a context.
  */
 int ecoserve_attn_prefill(ecoserve_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
                           const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
