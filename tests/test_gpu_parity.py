@@ -387,6 +387,12 @@ def test_empty_batches_and_host_side_errors():
         mis = torch.empty(qd.numel() + 8, dtype=torch.bfloat16, device="cuda")[1:1 + qd.numel()].view_as(qd)
         c.attn_prefill(mis, layer.kc, layer.vc, cu, cb, bt, torch.empty_like(qd))
     assert e.value.status == binding.EINVAL
+    # more new tokens than the pool holds: the prefill tile list has no room (checked before any launch)
+    with pytest.raises(binding.EcoserveError) as e:
+        T_big = 128 * (pb.num_blocks // 8 + 3 + 1)
+        huge = torch.empty((T_big, model.Hq, model.D), dtype=torch.bfloat16, device="cuda")
+        c.attn_prefill(huge, layer.kc, layer.vc, cu, cb, bt, torch.empty_like(huge), max_q_len=T_big)
+    assert e.value.status == binding.EINVAL
     # device-resident contents: the debug validator sees what the hot calls do not check
     total = dev_i32(pb.q_len)
     assert c.debug_validate(cu, total, bt) == binding.OK
