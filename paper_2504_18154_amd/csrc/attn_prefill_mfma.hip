@@ -121,6 +121,9 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // as two 32-key accumulators; the maximum is combined across the two lane halves.
 __device__ __forceinline__ float mask_and_max(f32x16 (&s)[2], int k0, int half, int pos, bool masked) {
   if (masked) {
+    // (an empty asm statement keeps this a real branch: turned into 32 unconditional selects it
+    // would run on every step, and only the two steps at the diagonal of an item need it)
+    asm volatile("" ::: "memory");
     // key index inside the step minus the lane-dependent part, against the bound moved the same
     // way: the comparisons take literal constants and one register
     const int bound = pos - k0 - half * 8;
