@@ -15,10 +15,10 @@
 // processed the workgroup already fetches the first K/V steps and the query rows of its next
 // item, so a change of item costs no memory round trip: with the short prompts of a
 // lognormal batch the start-up of a workgroup (tile lookup, block ids, first tiles, output
-// write-back) would otherwise take a fifth of the kernel's time.  Items are dealt so that
-// consecutive ones differ first in the K/V head and a workgroup prefers the items whose
-// index is congruent to its XCD (workgroup ids are dealt round-robin to the 8 XCDs): with 8
-// K/V heads each XCD's L2 holds one head's K/V.
+// write-back) would otherwise take a fifth of the kernel's time.  Consecutive items differ
+// first in the K/V head, and a workgroup serves the items whose index is congruent to its
+// XCD (workgroup ids are dealt round-robin to the 8 XCDs): with 8 K/V heads each XCD's L2
+// holds one head's K/V.
 //
 // Per 64-key step the four 16-token cache blocks of K and of V go straight from global
 // memory into LDS (global_load ... lds, 16 bytes per lane, double buffered, one barrier per
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
                                                                     const int32_t* __restrict__ ctx_before,
                                                                     const int32_t* __restrict__ block_table,
                                                                     int bt_stride, int B, int n_main_wgs,
-                                                                    int32_t* __restrict__ plan) {
+                                                                    int max_tiles, int32_t* __restrict__ plan) {
   __shared__ int pre[kMaxBatch + 1];
   __shared__ int bins[kPlanBins];
   __shared__ int wsum[kPlanThreads / 64];
@@ -214,6 +214,8 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     if (b0 + i < B) local += tiles_of(b0 + i);
   int n_tiles_all;
   int run = block_scan(local, n_tiles_all);
+  // never more records than the host sized the launch (and the plan buffer) for, whatever cu_q says
+  n_tiles_all = min(n_tiles_all, max_tiles);
   for (int i = 0; i < per; ++i)
     if (b0 + i < B) {
       pre[b0 + i] = run;
@@ -650,7 +652,7 @@ hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int
   if (n_items > 0x7fffffffLL - (1 << 20)) return hipErrorInvalidValue;
   const int64_t n_wg = n_items < n_persistent_wgs ? n_items : n_persistent_wgs;
   hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, cu_q, ctx_before, a.block_table,
-                     a.bt_stride, a.B, (int)n_wg, ws_plan);
+                     a.bt_stride, a.B, (int)n_wg, (int)max_tiles, ws_plan);
   hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q,
                      (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
                      a.lse, ws_plan, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)), make_divisor((uint32_t)a.Hkv),
