@@ -20,6 +20,8 @@
 // The destination blocks of the whole batch are numbered sequence after sequence; the grid
 // covers an upper bound on their number that the host can compute (T/16 + 2 per sequence),
 // and every workgroup finds its (sequence, block) from a prefix sum over the batch.
+// A call that brings at most one token per sequence (the decode step) takes a leaner kernel:
+// one wavefront per (sequence, K/V head), no numbering, no staging.
 #include "common.h"
 
 namespace eco {
@@ -59,7 +61,7 @@ __device__ __forceinline__ void scan_touched_blocks(int* pre, int* wsum, const i
   __syncthreads();
 }
 
-template <typename E, bool kOneToken>
+template <typename E>
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
                                                                     const E* __restrict__ k_new,
                                                                     const E* __restrict__ v_new,
@@ -72,24 +74,14 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
   __shared__ int pre[kMaxBatch + 1];
   __shared__ int wsum[kAppendThreads / 64];
   __shared__ __attribute__((aligned(16))) E vt[16][256 + X];  // staged V rows (D <= 256), padded
-  int b, first_unit;
-  if (kOneToken) {
-    // at most one new token per sequence (decode step): sequence b touches at most one block,
-    // so workgroup b serves sequence b and no numbering is needed
-    b = blockIdx.x;
-    first_unit = b;
-    if (cu_q[b + 1] - cu_q[b] <= 0) return;
-  } else {
-    scan_touched_blocks(pre, wsum, cu_q, ctx_before, B);
-    if ((int)blockIdx.x >= pre[B]) return;
-    int lo_b = 0, hi_b = B;
-    while (hi_b - lo_b > 1) {
-      const int mid = (lo_b + hi_b) >> 1;
-      if (pre[mid] <= (int)blockIdx.x) lo_b = mid; else hi_b = mid;
-    }
-    b = lo_b;
-    first_unit = pre[b];
+  scan_touched_blocks(pre, wsum, cu_q, ctx_before, B);
+  if ((int)blockIdx.x >= pre[B]) return;
+  int lo_b = 0, hi_b = B;
+  while (hi_b - lo_b > 1) {
+    const int mid = (lo_b + hi_b) >> 1;
+    if (pre[mid] <= (int)blockIdx.x) lo_b = mid; else hi_b = mid;
   }
+  const int b = lo_b, first_unit = pre[b];
   const int unit = blockIdx.x;  // destination block number within the batch
   const int g = blockIdx.y, tid = threadIdx.x;
   const int tok0 = cu_q[b], S = cu_q[b + 1] - tok0, cb = ctx_before[b];
@@ -135,20 +127,49 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
   }
 }
 
+// At most one new token per sequence (the decode step): one wavefront per (sequence, K/V head)
+// copies the token's K row as 16-byte units and scatters its V row into the slot's column.
+template <typename E>
+__global__ __launch_bounds__(kAppendThreads) void kv_append_one_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
+                                                                        const E* __restrict__ k_new,
+                                                                        const E* __restrict__ v_new,
+                                                                        const int32_t* __restrict__ cu_q,
+                                                                        const int32_t* __restrict__ ctx_before,
+                                                                        const int32_t* __restrict__ block_table,
+                                                                        int bt_stride, int B, int Hkv, int D) {
+  constexpr int X = Elem<E>::X;
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  const int pair = blockIdx.x * (kAppendThreads / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (pair >= B * Hkv) return;
+  const int b = pair / Hkv, g = pair % Hkv;
+  const int tok = cu_q[b];
+  if (cu_q[b + 1] - tok <= 0) return;
+  const int p = ctx_before[b], slot = p & 15;
+  const int64_t blk = block_table[(size_t)b * bt_stride + (p >> 4)];
+  const E* ksrc = k_new + ((size_t)tok * Hkv + g) * D;
+  E* kdst = k_cache + ((size_t)blk * Hkv + g) * 16 * D + (size_t)slot * X;
+  for (int c = lane; c < D / X; c += 64)
+    *reinterpret_cast<u4*>(kdst + (size_t)c * 16 * X) = *reinterpret_cast<const u4*>(ksrc + c * X);
+  const E* vsrc = v_new + ((size_t)tok * Hkv + g) * D;
+  E* vdst = v_cache + ((size_t)blk * Hkv + g) * D * 16 + slot;
+  for (int d = lane; d < D; d += 64) vdst[(size_t)d * 16] = vsrc[d];
+}
+
 template <typename E>
 static void launch_typed(const ecoserve_layout& L, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
                          const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
                          int32_t bt_stride, int32_t B, int32_t T, int32_t max_new_len, hipStream_t s) {
   if (max_new_len <= 1) {
-    const dim3 grid((unsigned)B, (unsigned)L.num_kv_heads);
-    hipLaunchKernelGGL((kv_append_kernel<E, true>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
+    const int per_wg = kAppendThreads / 64;
+    const dim3 grid((unsigned)(((int64_t)B * L.num_kv_heads + per_wg - 1) / per_wg));
+    hipLaunchKernelGGL((kv_append_one_kernel<E>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
                        (const E*)k_new, (const E*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
                        L.num_kv_heads, L.head_dim);
   } else {
     // a sequence with S new tokens touches at most S/16 + 2 blocks (ragged at both ends), and none if S == 0
     const int64_t max_units = (int64_t)T / 16 + 2 * (int64_t)(B < T ? B : T);
     const dim3 grid((unsigned)max_units, (unsigned)L.num_kv_heads);
-    hipLaunchKernelGGL((kv_append_kernel<E, false>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
+    hipLaunchKernelGGL((kv_append_kernel<E>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
                        (const E*)k_new, (const E*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
                        L.num_kv_heads, L.head_dim);
   }
