@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libecoserve.so")
+# ECOSERVE_LIB overrides the library to load (to compare builds); the default is the one built in-tree
+LIB_PATH = os.environ.get("ECOSERVE_LIB") or os.path.join(_HERE, "libecoserve.so")
 
 OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP, ECONTENT = range(6)
 BF16, F32 = 0, 1
