@@ -102,7 +102,14 @@ enum {
    * within the tolerance of the split-context merge but are no longer bit-identical from call
    * to call, because the cut points move with the measurements.  0 (default): equal shares,
    * bit-reproducible. */
-  ECOSERVE_OPT_DECODE_ADAPTIVE = 4
+  ECOSERVE_OPT_DECODE_ADAPTIVE = 4,
+  /* 1: consecutive ecoserve_attn_prefill calls (bf16, head size 128) that pass the same cu_q,
+   * ctx_before and block_table pointers, bt_stride, B and T are taken to describe the same
+   * batch - the caller vouches that the arrays' contents have not changed - and share the list
+   * of query tiles that the first of them builds, instead of each building its own (the layers
+   * of one step of a model: the list depends only on these arrays).  0 (default): every call
+   * builds its list.  Setting the option, to either value, forgets the current list. */
+  ECOSERVE_OPT_PREFILL_REUSE_PLAN = 5
 };
 
 enum { ECOSERVE_KERNEL_APPEND = 0, ECOSERVE_KERNEL_PREFILL = 1, ECOSERVE_KERNEL_DECODE = 2 };

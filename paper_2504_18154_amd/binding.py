@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("ECOSERVE_LIB") or os.path.join(_HERE, "libecoserve.so
 
 OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP, ECONTENT = range(6)
 BF16, F32 = 0, 1
-OPT_DECODE_SPLIT_TOKENS, OPT_FORCE_PLAIN, OPT_PROFILE, OPT_DECODE_ADAPTIVE = 1, 2, 3, 4
+OPT_DECODE_SPLIT_TOKENS, OPT_FORCE_PLAIN, OPT_PROFILE, OPT_DECODE_ADAPTIVE, OPT_PREFILL_REUSE_PLAN = 1, 2, 3, 4, 5
 KERNEL_APPEND, KERNEL_PREFILL, KERNEL_DECODE = 0, 1, 2
 
 EXPORTS = [

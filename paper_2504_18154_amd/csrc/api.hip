@@ -62,6 +62,7 @@ int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
   c->ws_ml = nullptr;
   c->ws_meta = nullptr;
   c->ws_plan = nullptr;
+  c->plan_key.valid = false;
   c->ws_splits = 0;
   c->ws_bytes = 0;
   const size_t slots = (size_t)c->max_batch * c->lay.num_q_heads * splits;
@@ -189,6 +190,9 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   c->opt_force_plain = 0;
   c->opt_profile = 0;
   c->opt_adaptive = 0;
+  c->opt_reuse_plan = 0;
+  c->plan_parity = 0;
+  c->plan_key.valid = false;
   c->share_parity = 0;
   c->ws_share = nullptr;
   c->ws_acc = nullptr;
@@ -249,6 +253,10 @@ int ecoserve_set_option(ecoserve_ctx* c, int32_t option, int32_t value) {
     case ECOSERVE_OPT_DECODE_ADAPTIVE:
       c->opt_adaptive = value ? 1 : 0;
       return ECOSERVE_OK;
+    case ECOSERVE_OPT_PREFILL_REUSE_PLAN:
+      c->opt_reuse_plan = value ? 1 : 0;
+      c->plan_key.valid = false;
+      return ECOSERVE_OK;
     default:
       return ECOSERVE_EINVAL;
   }
@@ -308,7 +316,25 @@ int ecoserve_attn_prefill(ecoserve_ctx* c, const void* q, const void* k_cache, c
   ProfileScope prof(c, ECOSERVE_KERNEL_PREFILL, s);
   hipError_t e;
   if (use_mfma(c)) {
-    e = launch_prefill_mfma(a, cu_q, ctx_before, T, max_q_len, c->ws_plan, c->num_cu * kPrefillWgsPerCu, s);
+    // The tile list depends only on the batch arrays.  With ECOSERVE_OPT_PREFILL_REUSE_PLAN the caller
+    // vouches that calls naming the same arrays, B and T see the same contents (the layers of one step),
+    // and the list of the first such call serves the following ones.
+    const int32_t n_wgs = c->num_cu * kPrefillWgsPerCu;
+    const int32_t grid = prefill_mfma_grid(a, T, n_wgs);
+    auto& key = c->plan_key;
+    const bool same = c->opt_reuse_plan && key.valid && key.cu_q == cu_q && key.ctx_before == ctx_before &&
+                      key.block_table == block_table && key.bt_stride == bt_stride && key.B == B && key.T == T &&
+                      key.n_wg == grid;
+    e = launch_prefill_mfma(a, cu_q, ctx_before, T, max_q_len, c->ws_plan, n_wgs, !same, c->plan_parity, s);
+    c->plan_parity ^= 1;
+    key.valid = e == hipSuccess;
+    key.cu_q = cu_q;
+    key.ctx_before = ctx_before;
+    key.block_table = block_table;
+    key.bt_stride = bt_stride;
+    key.B = B;
+    key.T = T;
+    key.n_wg = grid;
   } else
     e = launch_prefill_plain(a, cu_q, ctx_before, T, s);
   return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;

@@ -170,9 +170,11 @@ __device__ __forceinline__ void exp_tile(const f32x16& s, bf16x8 (&pf)[2], float
 
 // ---- plan: the query tiles of a batch, heaviest first ------------------------------------------
 //
-// Plan layout (int32): [0] number of query tiles, [kPlanCounter0 + kPlanCounterStride * i] ticket
-// counter of work queue i (one cache line each), then from kPlanHeaderInts one record of kRecInts
-// per query tile:
+// Plan layout (int32): [0] number of query tiles, [kPlanCounter0 + kPlanCounterStride * (kQueues * p
+// + i)] ticket counter of work queue i in counter set p (one cache line each; launches alternate
+// between the two sets and each launch leaves the other set ready for the next, so a tile list can
+// serve many launches without being rebuilt), then from kPlanHeaderInts one record of kRecInts per
+// query tile:
 //   0 sequence, 1 tile inside the sequence, 2 first packed token of the sequence, 3 S,
 //   4 ctx_before, 5 number of 64-key steps, 8..19 physical ids of the sequence's first 12 blocks
 // (clamped to its last block), i.e. everything a workgroup needs to start on the tile with one
@@ -279,7 +281,8 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
   }
   if (tid == 0) plan[0] = n_tiles_all;
   // each workgroup of the attention kernel owns the first two tickets of its queue outright
-  if (tid < kQueues) plan[kPlanCounter0 + kPlanCounterStride * tid] = 2 * ((n_main_wgs - tid + kQueues - 1) / kQueues);
+  if (tid < 2 * kQueues)
+    plan[kPlanCounter0 + kPlanCounterStride * tid] = 2 * ((n_main_wgs - tid % kQueues + kQueues - 1) / kQueues);
 }
 
 // Wave-uniform description of one work item (a query tile of one query head).
@@ -309,7 +312,8 @@ __device__ __forceinline__ Item describe(int rec, int g, int h, const int32_t* _
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, uint16_t* __restrict__ out, float* __restrict__ lse,
-    int32_t* __restrict__ plan, int Hq, int Hkv, int G, Divisor div_heads, Divisor div_hkv, float scale_log2e) {
+    int32_t* __restrict__ plan, int parity, int Hq, int Hkv, int G, Divisor div_heads, Divisor div_hkv,
+    float scale_log2e) {
   __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes + 16];
   char* const kbufs = smem;
   char* const vbufs = smem + 2 * kKTileBytes;
@@ -334,7 +338,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   // other, and hundreds of workgroups asking the same counter at the same moment wait tens of
   // microseconds.
   const int queue = blockIdx.x % kQueues;
-  int* const counter = plan + kPlanCounter0 + kPlanCounterStride * queue;
+  int* const counter = plan + kPlanCounter0 + kPlanCounterStride * (kQueues * parity + queue);
+  // the other counter set is idle (the launch that used it is over): start it for the next launch
+  if (blockIdx.x == 0 && threadIdx.x < kQueues)
+    plan[kPlanCounter0 + kPlanCounterStride * (kQueues * (parity ^ 1) + threadIdx.x)] =
+        2 * (((int)gridDim.x - (int)threadIdx.x + kQueues - 1) / kQueues);
   auto resolve = [&](int k) -> int {  // ticket k of the own queue -> item, -1 past the end
     const int f = kQueues * k + queue;
     return f < n_flat ? f : -1;
@@ -642,20 +650,31 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   }
 }
 
-hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
-                               int32_t /*max_q_len*/, int32_t* ws_plan, int32_t n_persistent_wgs, hipStream_t s) {
-  const int G = a.Hq / a.Hkv;
+// Workgroups of the attention launch: the persistent grid, or fewer if the batch cannot hold that
+// many items (0: nothing to do, -1: too many items to number).
+int32_t prefill_mfma_grid(const AttnArgs& a, int32_t T, int32_t n_persistent_wgs) {
   // sum over sequences of ceil(S_b / kTQ) <= T / kTQ + (number of non-empty sequences)
+  const int64_t n_items = prefill_plan_tiles(a.B, T) * a.Hq;
+  if (n_items <= 0) return 0;
+  if (n_items > 0x7fffffffLL - (1 << 20)) return -1;
+  return (int32_t)(n_items < n_persistent_wgs ? n_items : n_persistent_wgs);
+}
+
+hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
+                               int32_t /*max_q_len*/, int32_t* ws_plan, int32_t n_persistent_wgs, bool make_plan,
+                               int parity, hipStream_t s) {
+  const int G = a.Hq / a.Hkv;
   const int64_t max_tiles = prefill_plan_tiles(a.B, T);
-  const int64_t n_items = max_tiles * G * a.Hkv;
-  if (n_items <= 0) return hipSuccess;
-  if (n_items > 0x7fffffffLL - (1 << 20)) return hipErrorInvalidValue;
-  const int64_t n_wg = n_items < n_persistent_wgs ? n_items : n_persistent_wgs;
-  hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, cu_q, ctx_before, a.block_table,
-                     a.bt_stride, a.B, (int)n_wg, (int)max_tiles, ws_plan);
+  const int32_t n_wg = prefill_mfma_grid(a, T, n_persistent_wgs);
+  if (n_wg == 0) return hipSuccess;
+  if (n_wg < 0) return hipErrorInvalidValue;
+  if (make_plan)
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, cu_q, ctx_before, a.block_table,
+                       a.bt_stride, a.B, (int)n_wg, (int)max_tiles, ws_plan);
   hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q,
                      (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
-                     a.lse, ws_plan, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)), make_divisor((uint32_t)a.Hkv),
+                     a.lse, ws_plan, parity, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)),
+                     make_divisor((uint32_t)a.Hkv),
                      a.scale_log2e);
   return hipGetLastError();
 }

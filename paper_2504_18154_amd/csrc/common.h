@@ -21,7 +21,7 @@ constexpr int kPrefillWgsPerCu = 2;   // persistent prefill grid: workgroups per
 constexpr int kPlanMaxQueues = 8;     // prefill plan: most work queues
 constexpr int kPlanCounter0 = 32;     // prefill plan: first queue counter; each counter has a cache line of its own
 constexpr int kPlanCounterStride = 32;
-constexpr int kPlanHeaderInts = kPlanCounter0 + kPlanCounterStride * kPlanMaxQueues;  // then the records
+constexpr int kPlanHeaderInts = kPlanCounter0 + kPlanCounterStride * 2 * kPlanMaxQueues;  // two counter sets, then the records
 constexpr int kRecInts = 20;          // prefill plan: int32 fields per query-tile record
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -65,6 +65,7 @@ struct ecoserve_ctx {
   int32_t opt_force_plain;
   int32_t opt_profile;
   int32_t opt_adaptive;        // decode: per-XCD shares of the stream follow measured speeds
+  int32_t opt_reuse_plan;      // prefill: calls that name the same batch arrays share one tile list
   // split-context workspace: unnormalised partial outputs and (max, sum) pairs
   float* ws_acc;               // [max_batch][Hq][ws_splits][D]
   float* ws_ml;                // [max_batch][Hq][ws_splits][2]
@@ -74,6 +75,12 @@ struct ecoserve_ctx {
   int32_t ws_splits;
   int32_t* ws_plan;            // prefill plan: header and one record per query tile of the last prefill launch
   int64_t plan_tiles;          // records ws_plan has room for
+  int plan_parity;             // which of the plan's two sets of queue counters the next prefill launch takes
+  struct {                     // the batch the tile list in ws_plan was made for (valid = false: none)
+    bool valid;
+    const int32_t *cu_q, *ctx_before, *block_table;
+    int32_t bt_stride, B, T, n_wg;
+  } plan_key;
   size_t ws_bytes;
   // profiling
   std::vector<eco::EventPair> ev[3];
@@ -125,9 +132,12 @@ hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, cons
                                     const int32_t* ws_wave, int32_t n_waves, hipStream_t s);
 
 // attn_prefill_mfma.hip: bf16, D = 128
-// (ws_plan must hold kPlanHeaderInts + prefill_plan_tiles(B, T) * kRecInts int32)
+// (ws_plan must hold kPlanHeaderInts + prefill_plan_tiles(B, T) * kRecInts int32; make_plan false: the tile list
+// of an earlier launch for the same batch and grid is still in ws_plan; parity alternates from launch to launch)
+int32_t prefill_mfma_grid(const AttnArgs& a, int32_t T, int32_t n_persistent_wgs);
 hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
-                               int32_t max_q_len, int32_t* ws_plan, int32_t n_persistent_wgs, hipStream_t s);
+                               int32_t max_q_len, int32_t* ws_plan, int32_t n_persistent_wgs, bool make_plan,
+                               int parity, hipStream_t s);
 
 }  // namespace eco
 

@@ -256,6 +256,65 @@ def test_bf16_short_chunk_after_long_prefix():
     layer.close()
 
 
+def test_bf16_prefill_reuses_the_tile_list_across_layers():
+    """Several 'layers' (different caches and queries, the same batch arrays) with the tile list
+    built once and reused, against the oracle and bit for bit against the mode that rebuilds it;
+    then another batch through the same context, which must get a list of its own."""
+    from paper_2504_18154_amd import binding
+    model = M30
+    q_len = [700, 130, 1, 257, 0, 64, 2100]
+    say(f"bf16 prefill, tile list reused over 3 layers: {q_len}")
+    pb, layer = _mk(model, q_len, seed=61)
+    cu, cb, bt = dev_i32(pb.cu_q), dev_i32(pb.ctx_before), dev_i32(pb.block_table)
+    layers = []
+    for l in range(3):
+        q, k, v = _qkv(model, pb.T, 610 + 10 * l)
+        kc, vc = layer.ctx.new_cache()
+        layer.ctx.kv_append(kc, vc, k.cuda(), v.cuda(), cu, cb, bt)
+        layers.append((q.cuda(), kc, vc))
+    # layer 0 also lives in the Layer object, for the oracle
+    q0, k0, v0 = _qkv(model, pb.T, 610)
+    layer.append(k0, v0, pb.cu_q, pb.ctx_before, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q0, pb.cu_q, pb.ctx_before, pb.block_table)
+
+    def run_all():
+        outs = []
+        for qd, kc, vc in layers:
+            out = torch.full_like(qd, float("nan"))
+            lse = torch.full(qd.shape[:2], float("nan"), dtype=torch.float32, device="cuda")
+            layer.ctx.attn_prefill(qd, kc, vc, cu, cb, bt, out, lse, max_q_len=int(pb.q_len.max()))
+            outs.append((out, lse))
+        torch.cuda.synchronize()
+        return outs
+
+    fresh = run_all()
+    layer.ctx.set_option(binding.OPT_PREFILL_REUSE_PLAN, 1)
+    for rep in range(2):
+        reused = run_all()
+        for (a, al), (b, bl) in zip(fresh, reused):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(al, bl), "reused tile list changed the result"
+    compare("layer 0 with reused list", reused[0][0], ref, "bf16")
+    compare_lse("layer 0 with reused list", reused[0][1], ref_lse, "bf16")
+    # the same batch through other arrays: a list of its own, same result
+    cu2, cb2, bt2 = cu.clone(), cb.clone(), bt.clone()
+    qd, kc, vc = layers[1]
+    out = torch.full_like(qd, float("nan"))
+    layer.ctx.attn_prefill(qd, kc, vc, cu2, cb2, bt2, out, max_q_len=int(pb.q_len.max()))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), fresh[1][0].view(torch.int16))
+    # the same arrays but one sequence fewer: B and T differ, so the list is rebuilt
+    Bs, Ts = pb.B - 1, int(pb.cu_q[pb.B - 1])
+    qd, kc, vc = layers[0]
+    out = torch.full((Ts,) + tuple(qd.shape[1:]), float("nan"), dtype=qd.dtype, device="cuda")
+    lse = torch.full((Ts, model.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    layer.ctx.attn_prefill(qd[:Ts], kc, vc, cu[:Bs + 1], cb[:Bs], bt, out, lse, max_q_len=int(pb.q_len[:Bs].max()))
+    torch.cuda.synchronize()
+    ref_s, ref_s_lse = layer.prefill_oracle(q0[:Ts], pb.cu_q[:Bs + 1], pb.ctx_before[:Bs], pb.block_table[:Bs])
+    compare("one sequence fewer", out, ref_s, "bf16")
+    compare_lse("one sequence fewer", lse, ref_s_lse, "bf16")
+    layer.close()
+
+
 def test_bf16_decode_after_growth_steps():
     """Decode-only phase: several steps, each appending one token per sequence (crossing
     block boundaries) before attending."""
