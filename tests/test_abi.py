@@ -35,6 +35,24 @@ def test_library_exports_every_declared_symbol(binding):
     assert sorted(binding.EXPORTS) == names
 
 
+def test_binding_constants_match_the_header(binding):
+    """Options, status codes and kernel ids are plain integers on both sides of the boundary."""
+    text = open(HEADER).read()
+    header = {m.group(1): int(m.group(2)) for m in re.finditer(r"\b(ECOSERVE_[A-Z0-9_]+)\s*=\s*(\d+)", text)}
+    mine = {
+        "ECOSERVE_OPT_DECODE_SPLIT_TOKENS": binding.OPT_DECODE_SPLIT_TOKENS, "ECOSERVE_OPT_FORCE_PLAIN": binding.OPT_FORCE_PLAIN,
+        "ECOSERVE_OPT_PROFILE": binding.OPT_PROFILE, "ECOSERVE_OPT_DECODE_ADAPTIVE": binding.OPT_DECODE_ADAPTIVE,
+        "ECOSERVE_OPT_PREFILL_REUSE_PLAN": binding.OPT_PREFILL_REUSE_PLAN,
+        "ECOSERVE_OK": binding.OK, "ECOSERVE_EINVAL": binding.EINVAL, "ECOSERVE_ECONTENT": binding.ECONTENT,
+        "ECOSERVE_KERNEL_APPEND": binding.KERNEL_APPEND, "ECOSERVE_KERNEL_PREFILL": binding.KERNEL_PREFILL,
+        "ECOSERVE_KERNEL_DECODE": binding.KERNEL_DECODE,
+    }
+    for name, value in mine.items():
+        assert header.get(name) == value, f"{name}: header {header.get(name)} vs binding {value}"
+    options = {k for k in header if k.startswith("ECOSERVE_OPT_")}
+    assert options == {k for k in mine if k.startswith("ECOSERVE_OPT_")}, "an option of the header is missing in the binding"
+
+
 def test_strerror_and_cache_bytes(binding):
     assert binding.strerror(0) == "ok"
     assert "invalid" in binding.strerror(binding.EINVAL)
