@@ -315,6 +315,51 @@ def test_bf16_prefill_reuses_the_tile_list_across_layers():
     layer.close()
 
 
+@pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
+def test_bf16_seeded_random_batches(seed):
+    """Seeded random shapes: head counts, batch size, prefixes, prompt lengths (zeros, one token,
+    around the 16/64/128 boundaries, a few long ones), then two decode steps with per-XCD shares
+    on and off.  Everything against the oracle."""
+    from paper_2504_18154_amd import binding
+    rng = np.random.default_rng(seed)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 5, 8]))
+    model = wl.ModelShape(f"rnd{seed}", hkv * G, hkv, 128, 1, "bf16")
+    B = int(rng.integers(1, 24))
+    pool = np.array([0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 191, 200, 255, 256, 257, 600, 1100])
+    first = rng.choice(pool, size=B) * (rng.random(B) < 0.4)
+    second = rng.choice(pool, size=B)
+    first, second = first.astype(np.int64), second.astype(np.int64)
+    second[rng.integers(0, B)] = max(1, int(second.max()))      # at least one non-empty sequence
+    say(f"seed {seed}: {model.Hq}/{model.Hkv} heads, B={B}, prefix {first.tolist()}, new {second.tolist()}")
+    pb, layer = _mk(model, first + second, seed=seed, grow=2)
+    cu1, cu2 = wl.cu_from_lengths(first), wl.cu_from_lengths(second)
+    cb = first.astype(np.int32)
+    if int(cu1[-1]) > 0:
+        _, k1, v1 = _qkv(model, int(cu1[-1]), seed * 10)
+        layer.append(k1, v1, cu1, np.zeros(B, np.int32), pb.block_table)
+    q2, k2, v2 = _qkv(model, int(cu2[-1]), seed * 10 + 3)
+    layer.append(k2, v2, cu2, cb, pb.block_table)
+    layer.assert_cache_bit_exact()
+    out, lse = layer.prefill_gpu(q2, cu2, cb, pb.block_table)
+    ref, ref_lse = layer.prefill_oracle(q2, cu2, cb, pb.block_table)
+    compare("prefill", out, ref, "bf16")
+    compare_lse("prefill", lse, ref_lse, "bf16")
+    ctx = (first + second).astype(np.int32)
+    ones = wl.cu_from_lengths([1] * B)
+    for step in range(2):
+        q, k, v = _qkv(model, B, seed * 10 + 6 + step)
+        layer.append(k, v, ones, ctx, pb.block_table, max_new_len=1)
+        ctx = ctx + 1
+        layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, step)
+        out, lse = layer.decode_gpu(q, pb.block_table, ctx)
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+        compare(f"decode step {step}", out, ref, "bf16")
+        compare_lse(f"decode step {step}", lse, ref_lse, "bf16")
+    layer.assert_cache_bit_exact()
+    layer.close()
+
+
 def test_bf16_decode_after_growth_steps():
     """Decode-only phase: several steps, each appending one token per sequence (crossing
     block boundaries) before attending."""
