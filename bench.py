@@ -154,6 +154,8 @@ def main() -> int:
         t = [ev() for _ in range(3)]
         t[0].record()
         if do_pre:
+            # a step brings a new batch: its list of query tiles is built once, by the first layer's call
+            pctx.set_option(binding.OPT_PREFILL_REUSE_PLAN, 1)
             for l in range(layers):
                 kc, vc = p_pools[l]
                 if not p_chunks:
