@@ -584,7 +584,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     __syncthreads();  // K step 0 is consumed: its buffer receives step 2
 
     {
-      // the last step always takes its scores from sa: an odd number of plain steps comes in pairs after one single
+      // plain steps run in pairs (sa -> sb -> sa); the last step always takes its scores from sa, so a
+      // left-over single plain step is followed by a copy
       int j = 0;
       for (; j + 2 < cur.n_tiles; j += 2) {
         iteration(std::false_type(), j, sa, sb);
