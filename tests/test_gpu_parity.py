@@ -235,6 +235,27 @@ def test_bf16_large_batch_of_short_sequences():
     layer.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_append_at_the_largest_batch(dtype):
+    """4096 sequences (the largest batch a context accepts) of 0..40 new tokens behind 0..20 cached
+    ones: the append kernel's per-batch tables are at their largest; the cache is compared bit for bit."""
+    model = wl.ModelShape("small-heads", 4, 2, 128, 1, dtype)
+    rng = np.random.default_rng(43)
+    first = rng.integers(0, 21, size=4096)
+    second = rng.integers(0, 41, size=4096)
+    second[[0, 4095]] = [40, 33]
+    say(f"{dtype} append at batch 4096: {int(first.sum())} then {int(second.sum())} tokens")
+    pb, layer = _mk(model, first + second, seed=44)
+    cu1, cu2 = wl.cu_from_lengths(first), wl.cu_from_lengths(second)
+    _, k1, v1 = _qkv(model, int(cu1[-1]), 430)
+    layer.append(k1, v1, cu1, np.zeros(4096, np.int32), pb.block_table)
+    layer.assert_cache_bit_exact()
+    _, k2, v2 = _qkv(model, int(cu2[-1]), 440)
+    layer.append(k2, v2, cu2, first.astype(np.int32), pb.block_table)
+    layer.assert_cache_bit_exact()
+    layer.close()
+
+
 def test_bf16_short_chunk_after_long_prefix():
     """A few new tokens behind thousands of cached ones (one query tile, many key steps) next to a
     long new prompt: the work items differ by two orders of magnitude."""
