@@ -49,6 +49,8 @@ def main() -> int:
                     help="decode with equal chunks per wavefront instead of per-XCD shares that follow measured speeds")
     ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
                     help="run only one phase (profiling runs; the default is the full step)")
+    ap.add_argument("--no-probes", action="store_true",
+                    help="skip the two machine-ceiling probes (streaming read, matrix-core loop) after the timed region")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -289,6 +291,15 @@ def main() -> int:
                       f"fp64, {reps} repetitions, {cpu_s:.3f} s each",
             "seconds": cpu_s,
             "gpu_vs_oracle_layer0_max_abs": float(err.max()), "gpu_vs_oracle_layer0_mean_abs": float(err.mean()),
+        }
+    # ---------------- what this device sustains on the two rooflines' resources ------------
+    if not args.no_probes:
+        res["machine"] = {
+            "hbm_read_GBps": binding.probe_hbm_read(4 << 30, reps=5),
+            "mfma_bf16_TFLOPs": binding.probe_mfma_bf16(False, reps=5),
+            "mfma_bf16_random_operands_TFLOPs": binding.probe_mfma_bf16(True, reps=5),
+            "how": "after the timed region: 4 GiB read in 8 KiB pieces per wavefront, 16-byte loads; register-only 32x32x16 bf16 loop, "
+                   "4 wavefronts per SIMD, smooth and pseudo-random operands; 5 launches each after one untimed",
         }
     print(json.dumps(res))
     return 0

@@ -219,6 +219,28 @@ int ecoserve_debug_validate(ecoserve_ctx* ctx, const int32_t* cu_q, const int32_
 int ecoserve_profile_read(ecoserve_ctx* ctx, int32_t kernel, double* ms_total, int64_t* launches);
 int ecoserve_profile_reset(ecoserve_ctx* ctx);
 
+/*
+ * Machine ceilings for the roofline reasoning of Section 2.2 (Table 2 prices
+ * decode attention in bytes read, prefill attention in matrix FLOPs): what
+ * `device` sustains on each resource, to be reported beside the published
+ * peaks.  Measurement helpers, not hot calls: they allocate their own device
+ * memory, run on the null stream, synchronise the device and free everything
+ * before they return.  `reps` in [1, 1000] timed launches after one untimed.
+ *
+ * ecoserve_probe_hbm_read: reads a buffer of `bytes` (a multiple of 8192, at
+ *   least 1 MiB; use more than the 256 MiB last-level cache, e.g. 4 GiB) once
+ *   per launch, each wavefront taking whole 8 KiB pieces with coalesced
+ *   16-byte loads; *gb_per_s = bytes / mean launch time, in 1e9 B/s.
+ *   ECOSERVE_ENOMEM if the buffer cannot be allocated.
+ * ecoserve_probe_mfma_bf16: a register-only loop of 32x32x16 bf16 matrix
+ *   instructions, four wavefronts per SIMD; `random_operands` != 0 feeds every
+ *   accumulator chain its own pseudo-random operands (the chip then holds a
+ *   lower clock under its power limit than with smooth ones);
+ *   *tflop_per_s = FLOPs / mean launch time, in 1e12 FLOP/s.
+ */
+int ecoserve_probe_hbm_read(int device, size_t bytes, int32_t reps, double* gb_per_s);
+int ecoserve_probe_mfma_bf16(int device, int32_t random_operands, int32_t reps, double* tflop_per_s);
+
 #ifdef __cplusplus
 }
 #endif

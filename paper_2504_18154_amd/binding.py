@@ -25,7 +25,7 @@ EXPORTS = [
     "ecoserve_create", "ecoserve_destroy", "ecoserve_set_option", "ecoserve_strerror", "ecoserve_cache_bytes",
     "ecoserve_k_cache_index", "ecoserve_v_cache_index", "ecoserve_workspace_bytes", "ecoserve_kv_append",
     "ecoserve_attn_prefill", "ecoserve_attn_decode", "ecoserve_debug_validate", "ecoserve_profile_read",
-    "ecoserve_profile_reset",
+    "ecoserve_profile_reset", "ecoserve_probe_hbm_read", "ecoserve_probe_mfma_bf16",
 ]
 
 
@@ -65,6 +65,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.ecoserve_debug_validate.argtypes = [vp, i32p, i32p, i32p, i32, i32]
     lib.ecoserve_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ecoserve_profile_reset.argtypes = [vp]
+    lib.ecoserve_probe_hbm_read.argtypes = [ctypes.c_int, ctypes.c_size_t, i32, ctypes.POINTER(ctypes.c_double)]
+    lib.ecoserve_probe_mfma_bf16.argtypes = [ctypes.c_int, i32, i32, ctypes.POINTER(ctypes.c_double)]
     return lib
 
 
@@ -95,6 +97,22 @@ def k_cache_index(layout: Layout, blk, g, slot, d) -> int:
 
 def v_cache_index(layout: Layout, blk, g, slot, d) -> int:
     return int(_lib.ecoserve_v_cache_index(ctypes.byref(layout), blk, g, slot, d))
+
+
+def probe_hbm_read(nbytes: int = 4 << 30, reps: int = 5, device: int = 0) -> float:
+    """Sustained device-memory read rate of `device` in GB/s (1e9 bytes per second)."""
+    rate = ctypes.c_double()
+    _check(_lib.ecoserve_probe_hbm_read(int(device), int(nbytes), int(reps), ctypes.byref(rate)),
+           "ecoserve_probe_hbm_read")
+    return rate.value
+
+
+def probe_mfma_bf16(random_operands: bool, reps: int = 5, device: int = 0) -> float:
+    """Sustained bf16 matrix-core rate of `device` in TFLOP/s."""
+    rate = ctypes.c_double()
+    _check(_lib.ecoserve_probe_mfma_bf16(int(device), int(bool(random_operands)), int(reps), ctypes.byref(rate)),
+           "ecoserve_probe_mfma_bf16")
+    return rate.value
 
 
 def _ptr(t):

@@ -114,19 +114,6 @@ struct ProfileScope {
   }
 };
 
-struct DeviceGuard {
-  int prev;
-  bool ok;
-  explicit DeviceGuard(int dev) : prev(-1), ok(false) {
-    if (hipGetDevice(&prev) != hipSuccess) return;
-    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
-  }
-  ~DeviceGuard() {
-    int cur = -1;
-    if (ok && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
-  }
-};
-
 }  // namespace
 
 extern "C" {

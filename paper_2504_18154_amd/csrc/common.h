@@ -51,6 +51,20 @@ inline int64_t prefill_plan_tiles(int32_t B, int32_t T) {
   return (int64_t)T / kPrefillTileRows + (B < T ? B : T);
 }
 
+// Makes `dev` the calling thread's current device for a scope, and puts the previous one back.
+struct DeviceGuard {
+  int prev;
+  bool ok;
+  explicit DeviceGuard(int dev) : prev(-1), ok(false) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    int cur = -1;
+    if (ok && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
 }  // namespace eco
 
 struct ecoserve_ctx {

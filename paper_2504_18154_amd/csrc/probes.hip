@@ -1,0 +1,193 @@
+// Machine ceilings: what this GPU sustains on the two resources the paper's roofline
+// argument (Section 2.2, Table 2) prices attention against -- bytes read from device memory
+// (the decode phase) and bf16 matrix-core FLOPs (the prefill phase).  The published peaks are
+// the denominators of every reported fraction; these two short measurements say how much of
+// each peak any kernel could reach on the device at hand, so a reader can tell a kernel's
+// loss from the machine's.  They allocate and synchronise: measurement helpers, not hot calls.
+#include "common.h"
+
+namespace eco {
+
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kProbeThreads = 256;
+constexpr int kProbePiece = 8192;  // bytes one wavefront reads at a time
+constexpr int kMfmaChains = 4;     // independent accumulators per wavefront (hides the MFMA latency)
+constexpr int kMfmaIters = 20000;  // per launch: 4 chains x 20000 MFMAs per wavefront, a few milliseconds
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_fill_kernel(u4* __restrict__ dst, size_t n_vec) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+    const uint32_t h = probe_hash((uint32_t)i);
+    dst[i] = u4{h, h * 3u, h * 5u, h * 7u};
+  }
+}
+
+// Every 8 KiB piece of the buffer is read once, by one wavefront, as eight coalesced 16-byte
+// loads per lane (the access shape of a paged K/V block; grid-stride streaming measures some
+// 10% lower on this device).  Nothing is written unless the xor of all data hits one value.
+__global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const u4* __restrict__ src, size_t n_pieces,
+                                                                    u4* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const size_t n_waves = ((size_t)gridDim.x * blockDim.x) >> 6;
+  u4 acc = {0, 0, 0, 0};
+  for (size_t c = wave; c < n_pieces; c += n_waves) {
+    const u4* p = src + c * (kProbePiece / 16);
+#pragma unroll
+    for (int k = 0; k < kProbePiece / (64 * 16); ++k) acc ^= p[k * 64 + lane];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u && acc.x == 0x9e3779b9u) sink[lane] = acc;
+}
+
+// Register-only v_mfma_f32_32x32x16_bf16 loop.  With `random_operands` every chain multiplies
+// its own pseudo-random fragments (values in [-2, 2)); otherwise all chains share one pair of
+// smooth fragments.  The rates differ because the clock the chip holds under its power limit
+// depends on how many operand bits toggle.
+__global__ __launch_bounds__(kProbeThreads) void probe_mfma_kernel(float* __restrict__ sink, int iters,
+                                                                    int random_operands) {
+  bf16x8 a[kMfmaChains], b[kMfmaChains];
+#pragma unroll
+  for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (random_operands) {
+        const uint32_t h = probe_hash(threadIdx.x * 977u + blockIdx.x * 131u + c * 17u + i);
+        a[c][i] = (__bf16)(((int)(h & 0xffff) - 32768) / 16384.0f);
+        b[c][i] = (__bf16)(((int)(h >> 16) - 32768) / 16384.0f);
+      } else {
+        a[c][i] = (__bf16)(0.001f * (float)((threadIdx.x & 63) + i));
+        b[c][i] = (__bf16)(0.002f * (float)(i + 1));
+      }
+    }
+  f32x16 acc[kMfmaChains];
+#pragma unroll
+  for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c], b[c], acc[c], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[c][i];
+  if (s == 12345.678f) sink[threadIdx.x] = s;  // keeps the loop alive; practically never taken
+}
+
+struct ProbeTimer {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t init() {
+    hipError_t e = hipEventCreate(&e0);
+    return e != hipSuccess ? e : hipEventCreate(&e1);
+  }
+  ~ProbeTimer() {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  }
+};
+
+// One untimed launch, then `reps` launches between two events on the null stream.
+template <typename Launch>
+static hipError_t time_launches(Launch launch, int reps, double* ms_per_launch) {
+  ProbeTimer t;
+  hipError_t e = t.init();
+  if (e != hipSuccess) return e;
+  launch();
+  if ((e = hipDeviceSynchronize()) != hipSuccess) return e;
+  if ((e = hipEventRecord(t.e0, nullptr)) != hipSuccess) return e;
+  for (int r = 0; r < reps; ++r) launch();
+  if ((e = hipEventRecord(t.e1, nullptr)) != hipSuccess) return e;
+  if ((e = hipEventSynchronize(t.e1)) != hipSuccess) return e;
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  float ms = 0.f;
+  if ((e = hipEventElapsedTime(&ms, t.e0, t.e1)) != hipSuccess) return e;
+  *ms_per_launch = (double)ms / reps;
+  return hipSuccess;
+}
+
+static int probe_num_cu(int device, int* num_cu) {
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess) {
+    (void)hipGetLastError();
+    return ECOSERVE_EHIP;
+  }
+  if (device < 0 || device >= n) return ECOSERVE_EINVAL;
+  if (hipDeviceGetAttribute(num_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || *num_cu <= 0)
+    return ECOSERVE_EHIP;
+  return ECOSERVE_OK;
+}
+
+}  // namespace eco
+
+extern "C" {
+
+int ecoserve_probe_hbm_read(int device, size_t bytes, int32_t reps, double* gb_per_s) {
+  using namespace eco;
+  if (!gb_per_s || reps <= 0 || reps > 1000 || bytes < (1u << 20) || bytes % kProbePiece != 0)
+    return ECOSERVE_EINVAL;
+  int num_cu = 0;
+  if (int st = probe_num_cu(device, &num_cu)) return st;
+  DeviceGuard guard(device);
+  if (!guard.ok) return ECOSERVE_EHIP;
+  u4 *buf = nullptr, *sink = nullptr;
+  if (hipMalloc(&buf, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return ECOSERVE_ENOMEM;
+  }
+  if (hipMalloc(&sink, 64 * sizeof(u4)) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(buf);
+    return ECOSERVE_ENOMEM;
+  }
+  const size_t n_vec = bytes / 16;
+  const dim3 grid((unsigned)(num_cu * 8)), block(kProbeThreads);
+  hipLaunchKernelGGL(probe_fill_kernel, grid, block, 0, nullptr, buf, n_vec);
+  double ms = 0.0;
+  const hipError_t e = time_launches(
+      [&] { hipLaunchKernelGGL(probe_read_kernel, grid, block, 0, nullptr, buf, bytes / kProbePiece, sink); }, reps,
+      &ms);
+  (void)hipFree(buf);
+  (void)hipFree(sink);
+  if (e != hipSuccess) return ECOSERVE_EHIP;
+  *gb_per_s = (double)bytes / (ms * 1e-3) / 1e9;
+  return ECOSERVE_OK;
+}
+
+int ecoserve_probe_mfma_bf16(int device, int32_t random_operands, int32_t reps, double* tflop_per_s) {
+  using namespace eco;
+  if (!tflop_per_s || reps <= 0 || reps > 1000) return ECOSERVE_EINVAL;
+  int num_cu = 0;
+  if (int st = probe_num_cu(device, &num_cu)) return st;
+  DeviceGuard guard(device);
+  if (!guard.ok) return ECOSERVE_EHIP;
+  float* sink = nullptr;
+  if (hipMalloc(&sink, kProbeThreads * sizeof(float)) != hipSuccess) {
+    (void)hipGetLastError();
+    return ECOSERVE_ENOMEM;
+  }
+  const int wgs = num_cu * 4;  // four workgroups of four wavefronts per CU: four wavefronts per SIMD
+  double ms = 0.0;
+  const hipError_t e = time_launches(
+      [&] {
+        hipLaunchKernelGGL(probe_mfma_kernel, dim3(wgs), dim3(kProbeThreads), 0, nullptr, sink, kMfmaIters,
+                           random_operands ? 1 : 0);
+      },
+      reps, &ms);
+  (void)hipFree(sink);
+  if (e != hipSuccess) return ECOSERVE_EHIP;
+  const double flops = 2.0 * 32 * 32 * 16 * (double)kMfmaChains * kMfmaIters * (kProbeThreads / 64) * wgs;
+  *tflop_per_s = flops / (ms * 1e-3) / 1e12;
+  return ECOSERVE_OK;
+}
+
+}  // extern "C"

@@ -529,6 +529,24 @@ def test_empty_batches_and_host_side_errors():
     layer.close()
 
 
+def test_machine_ceiling_probes_report_plausible_rates():
+    """The two measurement helpers run, return rates of the right order for this class of device (between
+    a quarter of and the whole published peak: 8 TB/s, 2.5 PFLOP/s) and reject bad arguments."""
+    from paper_2504_18154_amd import binding
+    say("machine ceiling probes")
+    bw = binding.probe_hbm_read(1 << 30, reps=3)
+    smooth = binding.probe_mfma_bf16(False, reps=2)
+    rand = binding.probe_mfma_bf16(True, reps=2)
+    say(f"  read {bw:.0f} GB/s, bf16 MFMA {smooth:.0f} TFLOP/s (smooth operands), {rand:.0f} (random)")
+    assert 2000 < bw < 8000
+    assert 625 < rand <= smooth * 1.02 and smooth < 2520
+    for bad in (lambda: binding.probe_hbm_read(1000), lambda: binding.probe_hbm_read(1 << 30, reps=0),
+                lambda: binding.probe_hbm_read(1 << 30, device=99), lambda: binding.probe_mfma_bf16(True, reps=0)):
+        with pytest.raises(binding.EcoserveError) as ei:
+            bad()
+        assert ei.value.status == binding.EINVAL
+
+
 def test_profile_events_report_kernel_time():
     from paper_2504_18154_amd import binding
     model = M30
