@@ -49,6 +49,9 @@ def main() -> int:
                     help="decode with equal chunks per wavefront instead of per-XCD shares that follow measured speeds")
     ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
                     help="run only one phase (profiling runs; the default is the full step)")
+    ap.add_argument("--event-every", type=int, default=7,
+                    help="bracket every n-th launch of each kernel with HIP events inside the timed region (an event pair "
+                         "per launch delays the stream by several microseconds per layer; 1 = every launch)")
     ap.add_argument("--no-probes", action="store_true",
                     help="skip the two machine-ceiling probes (streaming read, matrix-core loop) after the timed region")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -186,7 +189,8 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     for c in (dctx, pctx):
-        c.set_option(binding.OPT_PROFILE, 1)
+        # chunked prefill makes calls of different sizes per layer: bracket them all
+        c.set_option(binding.OPT_PROFILE, 1 if args.prefill_chunk else max(1, args.event_every))
         c.profile_reset()
     timers = []
     torch.cuda.synchronize()
@@ -222,6 +226,8 @@ def main() -> int:
                         "block 16; append + attention per layer",
             "layers": layers, "phase": args.phase, "decode_shares": "equal" if args.equal_shares else "per-XCD, measured",
             "prefill_tile_list": "built once per step, shared by the layers",
+            "kernel_events": "every launch" if args.prefill_chunk or args.event_every <= 1
+                             else f"every {args.event_every}th launch of each kernel",
             "decode_batch": db.B, "decode_ctx_tokens": int(db.ctx_len.sum()),
             "prefill_prompts": pb.B, "prefill_tokens": pb.T, "prefill_lengths": [int(x) for x in pb.q_len],
         },

@@ -93,8 +93,12 @@ enum {
   ECOSERVE_OPT_DECODE_SPLIT_TOKENS = 1,
   /* 1: use the plain (non matrix-core) kernels even where the fast ones apply. */
   ECOSERVE_OPT_FORCE_PLAIN = 2,
-  /* 1: bracket the dominant kernel of each hot call with HIP events on the
-   * call's stream; read the sums with ecoserve_profile_read(). */
+  /* n >= 1: bracket the dominant kernel of every n-th hot call of each kind
+   * (counted from the last ecoserve_profile_reset(), the first one included)
+   * with HIP events on the call's stream; read the sums with
+   * ecoserve_profile_read().  0 (default): off.  An event pair delays the
+   * stream by a few microseconds, so a timed loop samples (n around 7)
+   * rather than bracketing every launch.  Negative: ECOSERVE_EINVAL. */
   ECOSERVE_OPT_PROFILE = 3,
   /* 1: decode (bf16, head size 128, built-in split) cuts the K/V stream into per-XCD shares that
    * follow the speeds measured in the context's earlier decode calls (the XCDs of one device
@@ -213,8 +217,9 @@ int ecoserve_debug_validate(ecoserve_ctx* ctx, const int32_t* cu_q, const int32_
 
 /*
  * With ECOSERVE_OPT_PROFILE on: synchronise, then return the summed duration
- * (milliseconds) and count of the dominant kernel of `kernel`
- * (ECOSERVE_KERNEL_*) since the last ecoserve_profile_reset().
+ * (milliseconds) and the number of the bracketed launches of the dominant
+ * kernel of `kernel` (ECOSERVE_KERNEL_*) since the last
+ * ecoserve_profile_reset().
  */
 int ecoserve_profile_read(ecoserve_ctx* ctx, int32_t kernel, double* ms_total, int64_t* launches);
 int ecoserve_profile_reset(ecoserve_ctx* ctx);

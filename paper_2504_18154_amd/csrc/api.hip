@@ -92,14 +92,14 @@ int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
   return ECOSERVE_OK;
 }
 
-// Profiling: a pair of events around the dominant kernel of a hot call.
+// Profiling: a pair of events around the dominant kernel of a hot call (of every n-th call of a kind).
 struct ProfileScope {
   ecoserve_ctx* c;
   int which;
   hipStream_t s;
   EventPair* ep;
   ProfileScope(ecoserve_ctx* ctx, int w, hipStream_t st) : c(ctx), which(w), s(st), ep(nullptr) {
-    if (!c->opt_profile) return;
+    if (!c->opt_profile || c->prof_seq[which]++ % (uint32_t)c->opt_profile != 0) return;
     if (c->ev_used[which] == c->ev[which].size()) {
       EventPair e;
       if (hipEventCreate(&e.start) != hipSuccess) return;
@@ -189,7 +189,7 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   c->plan_tiles = 0;
   c->ws_splits = 0;
   c->ws_bytes = 0;
-  for (int i = 0; i < 3; ++i) c->ev_used[i] = 0;
+  for (int i = 0; i < 3; ++i) c->ev_used[i] = 0, c->prof_seq[i] = 0;
   st = alloc_workspace(c, kMinSplitTokens);
   if (st != ECOSERVE_OK) { delete c; return st; }
   {
@@ -235,7 +235,8 @@ int ecoserve_set_option(ecoserve_ctx* c, int32_t option, int32_t value) {
       c->opt_force_plain = value ? 1 : 0;
       return ECOSERVE_OK;
     case ECOSERVE_OPT_PROFILE:
-      c->opt_profile = value ? 1 : 0;
+      if (value < 0) return ECOSERVE_EINVAL;
+      c->opt_profile = value;
       return ECOSERVE_OK;
     case ECOSERVE_OPT_DECODE_ADAPTIVE:
       c->opt_adaptive = value ? 1 : 0;
@@ -415,7 +416,7 @@ int ecoserve_profile_reset(ecoserve_ctx* c) {
   if (!c) return ECOSERVE_EINVAL;
   DeviceGuard guard(c->device);
   if (!guard.ok || hipDeviceSynchronize() != hipSuccess) return ECOSERVE_EHIP;
-  for (int i = 0; i < 3; ++i) c->ev_used[i] = 0;
+  for (int i = 0; i < 3; ++i) c->ev_used[i] = 0, c->prof_seq[i] = 0;
   return ECOSERVE_OK;
 }
 

@@ -77,7 +77,7 @@ struct ecoserve_ctx {
   // knobs
   int32_t opt_split_tokens;    // 0 = automatic
   int32_t opt_force_plain;
-  int32_t opt_profile;
+  int32_t opt_profile;         // 0 off, n: time every n-th hot call of each kind
   int32_t opt_adaptive;        // decode: per-XCD shares of the stream follow measured speeds
   int32_t opt_reuse_plan;      // prefill: calls that name the same batch arrays share one tile list
   // split-context workspace: unnormalised partial outputs and (max, sum) pairs
@@ -99,6 +99,7 @@ struct ecoserve_ctx {
   // profiling
   std::vector<eco::EventPair> ev[3];
   size_t ev_used[3];
+  uint32_t prof_seq[3];        // hot calls of each kind since the last profile reset (every opt_profile-th is timed)
 };
 
 namespace eco {

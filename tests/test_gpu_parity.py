@@ -562,4 +562,16 @@ def test_profile_events_report_kernel_time():
     assert n == 1 and ms > 0
     layer.ctx.profile_reset()
     assert layer.ctx.profile_read(binding.KERNEL_PREFILL) == (0.0, 0)
+    # every third call of a kind: calls 0, 3 and 6 of seven are bracketed, the appends count on their own
+    layer.ctx.set_option(binding.OPT_PROFILE, 3)
+    layer.ctx.profile_reset()
+    for i in range(7):
+        layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+        if i < 2:
+            layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    ms, n = layer.ctx.profile_read(binding.KERNEL_PREFILL)
+    assert n == 3 and 0 < ms < 1000
+    assert layer.ctx.profile_read(binding.KERNEL_APPEND)[1] == 1
+    with pytest.raises(binding.EcoserveError):
+        layer.ctx.set_option(binding.OPT_PROFILE, -1)
     layer.close()
