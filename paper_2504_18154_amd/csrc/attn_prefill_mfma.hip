@@ -117,6 +117,12 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
+// A row's keys are split between lane l and lane l ^ 32: the maximum over both.
+__device__ __forceinline__ float across_halves(float bm) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(bm), __float_as_uint(bm), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // Causal mask (if the tile touches the diagonal) and row maximum of a 64-key S^T tile held
 // as two 32-key accumulators; the maximum is combined across the two lane halves.
 __device__ __forceinline__ float mask_and_max(f32x16 (&s)[2], int k0, int half, int pos, bool masked) {
@@ -140,8 +146,7 @@ __device__ __forceinline__ float mask_and_max(f32x16 (&s)[2], int k0, int half, 
 #pragma unroll
   for (int i = 1; i < 15; i += 2) bm = max3(bm, s[1][i], s[1][i + 1]);
   bm = fmaxf(bm, s[1][15]);
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(bm), __float_as_uint(bm), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return across_halves(bm);
 }
 
 // Scores of one 32-key accumulator -> bf16 weights 2^(s c - mc) (two B-operand fragments of
@@ -470,6 +475,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
       bf16x8 pf0[2], pf1[2];
       const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
       float pv[2];
+      float bmx = 0.f;
       // 32 matrix instructions per step, in this order:
       //   slots  0..15  scores of step j+1: d step t = slot/2, 32-key half = slot%2
       //   slots 16..23  O += V P, keys  0..31 of step j: d tile = i%4, 16-key step = i/4
@@ -493,6 +499,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
         if (e & 1) {
           const bf16x2 a = {(__bf16)pv[0], (__bf16)pv[1]};
           l = __builtin_amdgcn_fdot2_f32_bf16(a, ones, l, false);
+          asm volatile("" : "+v"(l));  // keeps the sum in its slot (it would otherwise sink below the loop)
           pf[e >> 3][(e & 7) - 1] = a[0];
           pf[e >> 3][(e & 7)] = a[1];
         }
@@ -519,12 +526,28 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
         } else {
           const int i = s - 24;
           o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf1[i >> 2], o[i & 3], 0, 0, 0);
+          if constexpr (!is_last) {
+            // the next step's scores are complete since slot 17: their maximum (without a mask) is
+            // built here, four values per slot
+            auto val = [&](int k) { return sn[k >> 4][k & 15]; };
+            if (i == 0) {
+              bmx = max3(val(0), val(1), val(2));
+              bmx = max3(bmx, val(3), val(4));
+            } else if (i < 7) {
+              bmx = max3(bmx, val(4 * i + 1), val(4 * i + 2));
+              bmx = max3(bmx, val(4 * i + 3), val(4 * i + 4));
+            } else {
+              bmx = max3(bmx, val(29), val(30));
+              bmx = fmaxf(bmx, val(31));
+            }
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
       if constexpr (!is_last) {
         const int k0n = (j + 1) * kTK;
-        const float bm = mask_and_max(sn, k0n, half, pos, k0n + kTK - 1 > w_pmin);
+        // a step at the diagonal needs the mask first: its maximum is taken again from the masked scores
+        const float bm = k0n + kTK - 1 > w_pmin ? mask_and_max(sn, k0n, half, pos, true) : across_halves(bmx);
         if (__any((bm - m) * c > kTau)) {
           // the next step's scores exceed the exponent offset by more than 2^kTau: raise it
           const float m_new = fmaxf(m, bm);
