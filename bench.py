@@ -49,6 +49,9 @@ def main() -> int:
                     help="decode with equal chunks per wavefront instead of per-XCD shares that follow measured speeds")
     ap.add_argument("--phase", choices=["both", "decode", "prefill"], default="both",
                     help="run only one phase (profiling runs; the default is the full step)")
+    ap.add_argument("--fused-qkv", action="store_true",
+                    help="Q, K and V are slices of one row [Hq + 2 Hkv][D] per token (the output of a fused projection, "
+                         "Eq. 1) and are read in place through the strided calls; default: three packed arrays")
     ap.add_argument("--event-every", type=int, default=7,
                     help="bracket every n-th launch of each kernel with HIP events inside the timed region (an event pair "
                          "per launch delays the stream by several microseconds per layer; 1 = every launch)")
@@ -60,6 +63,10 @@ def main() -> int:
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no cross-GPU exchange step); "
               "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    if args.fused_qkv and args.prefill_chunk:
+        print("bench.py: --fused-qkv and --prefill-chunk are separate experiments; give one of them", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -129,6 +136,16 @@ def main() -> int:
         d_knew0, d_vnew0 = stream_k[last].contiguous(), stream_v[last].contiguous()
     d_out = torch.empty((layers, db.B, model.Hq, model.D), dtype=torch.bfloat16, device=dev)
 
+    def fuse(q, k, v):
+        """The same bits as slices of one [tokens, Hq + 2 Hkv, D] array."""
+        rows = torch.cat([q, k, v], dim=1)
+        return rows[:, :model.Hq], rows[:, model.Hq:model.Hq + model.Hkv], rows[:, model.Hq + model.Hkv:]
+
+    if args.fused_qkv:
+        if do_dec:
+            _, d_knew0, d_vnew0 = fuse(d_q, d_knew0, d_vnew0)
+        d_q, d_knew, d_vnew = fuse(d_q, d_knew, d_vnew)
+
     # ---------------- prefill-only batch (config index 2) --------------------------------
     pb = wl.config3_prefill_30b()
     pctx = binding.Context(model.Hq, model.Hkv, model.D, pb.num_blocks, "bf16", pb.B, pb.block_table.shape[1])
@@ -140,6 +157,11 @@ def main() -> int:
     p_k = wl.randn((pb.T, model.Hkv, model.D), "bf16", pb.seed + 4, device=dev)
     p_v = wl.randn((pb.T, model.Hkv, model.D), "bf16", pb.seed + 5, device=dev)
     p_out = torch.empty_like(p_q)
+    if args.fused_qkv:
+        p_q, p_k, p_v = fuse(p_q, p_k, p_v)
+    append = (lambda c: c.kv_append_strided) if args.fused_qkv else (lambda c: c.kv_append)
+    prefill = pctx.attn_prefill_strided if args.fused_qkv else pctx.attn_prefill
+    decode = dctx.attn_decode_strided if args.fused_qkv else dctx.attn_decode
     # chunked prefill: chunk ci holds tokens [ci C, ci C + C) of every prompt that is that long
     p_chunks = []
     if args.prefill_chunk > 0:
@@ -164,8 +186,8 @@ def main() -> int:
             for l in range(layers):
                 kc, vc = p_pools[l]
                 if not p_chunks:
-                    pctx.kv_append(kc, vc, p_k, p_v, p_cu, p_before, p_bt, max_new_len=pb.max_q_len)
-                    pctx.attn_prefill(p_q, kc, vc, p_cu, p_before, p_bt, p_out, max_q_len=pb.max_q_len)
+                    append(pctx)(kc, vc, p_k, p_v, p_cu, p_before, p_bt, max_new_len=pb.max_q_len)
+                    prefill(p_q, kc, vc, p_cu, p_before, p_bt, p_out, max_q_len=pb.max_q_len)
                 for ch in p_chunks:
                     pctx.kv_append(kc, vc, ch["k"], ch["v"], ch["cu"], ch["before"], p_bt, max_new_len=ch["max_len"])
                     pctx.attn_prefill(ch["q"], kc, vc, ch["cu"], ch["before"], p_bt, ch["out"], max_q_len=ch["max_len"])
@@ -174,8 +196,8 @@ def main() -> int:
             for l in range(layers):
                 kc, vc = d_pools[l]
                 kn, vn = (d_knew0, d_vnew0) if l == 0 else (d_knew, d_vnew)
-                dctx.kv_append(kc, vc, kn, vn, d_cu, d_before, d_bt, max_new_len=1)
-                dctx.attn_decode(d_q, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
+                append(dctx)(kc, vc, kn, vn, d_cu, d_before, d_bt, max_new_len=1)
+                decode(d_q, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
         t[2].record()
         if timers is not None:
             timers.append(t)
@@ -226,6 +248,8 @@ def main() -> int:
                         "block 16; append + attention per layer",
             "layers": layers, "phase": args.phase, "decode_shares": "equal" if args.equal_shares else "per-XCD, measured",
             "prefill_tile_list": "built once per step, shared by the layers",
+            "qkv_rows": "slices of fused rows [tokens, Hq + 2 Hkv, D], read in place" if args.fused_qkv
+                        else "three packed arrays",
             "kernel_events": "every launch" if args.prefill_chunk or args.event_every <= 1
                              else f"every {args.event_every}th launch of each kernel",
             "decode_batch": db.B, "decode_ctx_tokens": int(db.ctx_len.sum()),

@@ -225,6 +225,32 @@ int ecoserve_profile_read(ecoserve_ctx* ctx, int32_t kernel, double* ms_total, i
 int ecoserve_profile_reset(ecoserve_ctx* ctx);
 
 /*
+ * The three hot calls on rows that are not packed: Q, K and V read in place
+ * from the output of the projection of Eq. 1 (Section 2.1), which a fused
+ * projection writes as one row [Hq + 2 Hkv][D] per token.  The heads of one
+ * token stay contiguous ([H][D]); consecutive tokens are `*_row_stride`
+ * ELEMENTS apart: at least H * D, a multiple of 16 bytes, below 2^31.  For a
+ * fused row, k_new = qkv + Hq * D, v_new = qkv + (Hq + Hkv) * D and all three
+ * strides are (Hq + 2 Hkv) * D: no split copy of the projection output is
+ * needed before the cache append.  Everything else (outputs packed
+ * [T][Hq][D], errors, ownership) is as in the packed calls, which are these
+ * with the strides Hkv * D and Hq * D.  A stride that breaks the rules above:
+ * ECOSERVE_EINVAL.
+ */
+int ecoserve_kv_append_strided(ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
+                               const void* v_new, int64_t new_row_stride, const int32_t* cu_q,
+                               const int32_t* ctx_before, const int32_t* block_table, int32_t bt_stride,
+                               int32_t B, int32_t T, int32_t max_new_len, void* stream);
+int ecoserve_attn_prefill_strided(ecoserve_ctx* ctx, const void* q, int64_t q_row_stride, const void* k_cache,
+                                  const void* v_cache, const int32_t* cu_q, const int32_t* ctx_before,
+                                  const int32_t* block_table, int32_t bt_stride, void* out, float* lse,
+                                  int32_t B, int32_t T, int32_t max_q_len, void* stream);
+int ecoserve_attn_decode_strided(ecoserve_ctx* ctx, const void* q, int64_t q_row_stride, const void* k_cache,
+                                 const void* v_cache, const int32_t* block_table, int32_t bt_stride,
+                                 const int32_t* ctx_len, void* out, float* lse, int32_t B, int32_t max_ctx_len,
+                                 void* stream);
+
+/*
  * Machine ceilings for the roofline reasoning of Section 2.2 (Table 2 prices
  * decode attention in bytes read, prefill attention in matrix FLOPs): what
  * `device` sustains on each resource, to be reported beside the published

@@ -26,6 +26,7 @@ EXPORTS = [
     "ecoserve_k_cache_index", "ecoserve_v_cache_index", "ecoserve_workspace_bytes", "ecoserve_kv_append",
     "ecoserve_attn_prefill", "ecoserve_attn_decode", "ecoserve_debug_validate", "ecoserve_profile_read",
     "ecoserve_profile_reset", "ecoserve_probe_hbm_read", "ecoserve_probe_mfma_bf16",
+    "ecoserve_kv_append_strided", "ecoserve_attn_prefill_strided", "ecoserve_attn_decode_strided",
 ]
 
 
@@ -62,6 +63,10 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.ecoserve_kv_append.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, i32p, i32, i32, i32, i32, vp]
     lib.ecoserve_attn_prefill.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32, vp, vp, i32, i32, i32, vp]
     lib.ecoserve_attn_decode.argtypes = [vp, vp, vp, vp, i32p, i32, i32p, vp, vp, i32, i32, vp]
+    i64 = ctypes.c_int64
+    lib.ecoserve_kv_append_strided.argtypes = [vp, vp, vp, vp, vp, i64, i32p, i32p, i32p, i32, i32, i32, i32, vp]
+    lib.ecoserve_attn_prefill_strided.argtypes = [vp, vp, i64, vp, vp, i32p, i32p, i32p, i32, vp, vp, i32, i32, i32, vp]
+    lib.ecoserve_attn_decode_strided.argtypes = [vp, vp, i64, vp, vp, i32p, i32, i32p, vp, vp, i32, i32, vp]
     lib.ecoserve_debug_validate.argtypes = [vp, i32p, i32p, i32p, i32, i32]
     lib.ecoserve_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ecoserve_profile_reset.argtypes = [vp]
@@ -117,6 +122,13 @@ def probe_mfma_bf16(random_operands: bool, reps: int = 5, device: int = 0) -> fl
 
 def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _row_stride(t) -> int:
+    """Elements between consecutive tokens of a [tokens, heads, D] tensor or view whose heads are contiguous."""
+    if t.dim() != 3 or t.stride(2) != 1 or t.stride(1) != t.shape[2]:
+        raise ValueError("expected a [tokens, heads, D] tensor with contiguous heads")
+    return int(t.stride(0)) if t.shape[0] > 1 else int(t.shape[1] * t.shape[2])
 
 
 def _stream():
@@ -195,6 +207,37 @@ class Context:
                                           _ptr(ctx_before), _ptr(block_table), int(block_table.shape[1]), _ptr(out),
                                           _ptr(lse), int(B), int(T), int(max_q_len), _stream()),
                "ecoserve_attn_prefill")
+
+    # the same on views into wider rows (e.g. slices of a fused projection output [T, Hq + 2 Hkv, D])
+    def kv_append_strided(self, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, max_new_len=None):
+        B = ctx_before.numel()
+        T = k_new.shape[0]
+        if max_new_len is None:
+            max_new_len = T
+        if _row_stride(k_new) != _row_stride(v_new):
+            raise ValueError("k_new and v_new must have the same row stride")
+        _check(_lib.ecoserve_kv_append_strided(self._h, _ptr(k_cache), _ptr(v_cache), _ptr(k_new), _ptr(v_new),
+                                               _row_stride(k_new), _ptr(cu_q), _ptr(ctx_before), _ptr(block_table),
+                                               int(block_table.shape[1]), int(B), int(T), int(max_new_len),
+                                               _stream()), "ecoserve_kv_append_strided")
+
+    def attn_prefill_strided(self, q, k_cache, v_cache, cu_q, ctx_before, block_table, out, lse=None,
+                             max_q_len=None):
+        B = ctx_before.numel()
+        T = q.shape[0]
+        if max_q_len is None:
+            max_q_len = T
+        _check(_lib.ecoserve_attn_prefill_strided(self._h, _ptr(q), _row_stride(q), _ptr(k_cache), _ptr(v_cache),
+                                                  _ptr(cu_q), _ptr(ctx_before), _ptr(block_table),
+                                                  int(block_table.shape[1]), _ptr(out), _ptr(lse), int(B), int(T),
+                                                  int(max_q_len), _stream()), "ecoserve_attn_prefill_strided")
+
+    def attn_decode_strided(self, q, k_cache, v_cache, block_table, ctx_len, out, max_ctx_len, lse=None):
+        B = ctx_len.numel()
+        _check(_lib.ecoserve_attn_decode_strided(self._h, _ptr(q), _row_stride(q), _ptr(k_cache), _ptr(v_cache),
+                                                 _ptr(block_table), int(block_table.shape[1]), _ptr(ctx_len),
+                                                 _ptr(out), _ptr(lse), int(B), int(max_ctx_len), _stream()),
+               "ecoserve_attn_decode_strided")
 
     def attn_decode(self, q, k_cache, v_cache, block_table, ctx_len, out, max_ctx_len, lse=None):
         B = ctx_len.numel()

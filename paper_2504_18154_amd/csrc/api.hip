@@ -250,10 +250,27 @@ int ecoserve_set_option(ecoserve_ctx* c, int32_t option, int32_t value) {
   }
 }
 
+// A row stride in elements: at least the packed row, 16-byte multiples, 32-bit.
+static bool stride_ok(const ecoserve_ctx* c, int64_t stride, int32_t heads) {
+  const int64_t esize = c->lay.dtype == ECOSERVE_BF16 ? 2 : 4;
+  return stride >= (int64_t)heads * c->lay.head_dim && stride < (int64_t)1 << 31 && (stride * esize) % 16 == 0;
+}
+
 int ecoserve_kv_append(ecoserve_ctx* c, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
                        const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
                        int32_t bt_stride, int32_t B, int32_t T, int32_t max_new_len, void* stream) {
+  if (!c) return ECOSERVE_EINVAL;
+  return ecoserve_kv_append_strided(c, k_cache, v_cache, k_new, v_new,
+                                    (int64_t)c->lay.num_kv_heads * c->lay.head_dim, cu_q, ctx_before, block_table,
+                                    bt_stride, B, T, max_new_len, stream);
+}
+
+int ecoserve_kv_append_strided(ecoserve_ctx* c, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
+                               int64_t new_row_stride, const int32_t* cu_q, const int32_t* ctx_before,
+                               const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
+                               int32_t max_new_len, void* stream) {
   if (!c || B < 0 || T < 0 || max_new_len < 0) return ECOSERVE_EINVAL;
+  if (!stride_ok(c, new_row_stride, c->lay.num_kv_heads)) return ECOSERVE_EINVAL;
   if (B == 0 || T == 0) return ECOSERVE_OK;
   if (!k_cache || !v_cache || !k_new || !v_new || !cu_q || !ctx_before || !block_table) return ECOSERVE_EINVAL;
   if (B > c->max_batch || bt_stride <= 0 || max_new_len > T) return ECOSERVE_EINVAL;
@@ -262,15 +279,16 @@ int ecoserve_kv_append(ecoserve_ctx* c, void* k_cache, void* v_cache, const void
   if (!guard.ok) return ECOSERVE_EHIP;
   hipStream_t s = (hipStream_t)stream;
   ProfileScope prof(c, ECOSERVE_KERNEL_APPEND, s);
-  const hipError_t e = launch_kv_append(c, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride,
-                                        B, T, max_new_len, s);
+  const hipError_t e = launch_kv_append(c, k_cache, v_cache, k_new, v_new, (int32_t)new_row_stride, cu_q, ctx_before,
+                                        block_table, bt_stride, B, T, max_new_len, s);
   return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
 }
 
-static AttnArgs make_args(const ecoserve_ctx* c, const void* q, const void* k_cache, const void* v_cache,
+static AttnArgs make_args(const ecoserve_ctx* c, const void* q, int64_t q_row_stride, const void* k_cache, const void* v_cache,
                           const int32_t* block_table, int32_t bt_stride, void* out, float* lse, int32_t B) {
   AttnArgs a;
   a.q = q;
+  a.q_row_stride = (int32_t)q_row_stride;
   a.k_cache = k_cache;
   a.v_cache = v_cache;
   a.block_table = block_table;
@@ -290,7 +308,17 @@ int ecoserve_attn_prefill(ecoserve_ctx* c, const void* q, const void* k_cache, c
                           const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
                           int32_t bt_stride, void* out, float* lse, int32_t B, int32_t T, int32_t max_q_len,
                           void* stream) {
+  if (!c) return ECOSERVE_EINVAL;
+  return ecoserve_attn_prefill_strided(c, q, (int64_t)c->lay.num_q_heads * c->lay.head_dim, k_cache, v_cache, cu_q,
+                                       ctx_before, block_table, bt_stride, out, lse, B, T, max_q_len, stream);
+}
+
+int ecoserve_attn_prefill_strided(ecoserve_ctx* c, const void* q, int64_t q_row_stride, const void* k_cache,
+                                  const void* v_cache, const int32_t* cu_q, const int32_t* ctx_before,
+                                  const int32_t* block_table, int32_t bt_stride, void* out, float* lse, int32_t B,
+                                  int32_t T, int32_t max_q_len, void* stream) {
   if (!c || B < 0 || T < 0 || max_q_len < 0) return ECOSERVE_EINVAL;
+  if (!stride_ok(c, q_row_stride, c->lay.num_q_heads)) return ECOSERVE_EINVAL;
   if (B == 0 || T == 0) return ECOSERVE_OK;
   if (!q || !k_cache || !v_cache || !cu_q || !ctx_before || !block_table || !out) return ECOSERVE_EINVAL;
   if (B > c->max_batch || bt_stride <= 0 || max_q_len > T || max_q_len == 0) return ECOSERVE_EINVAL;
@@ -300,7 +328,7 @@ int ecoserve_attn_prefill(ecoserve_ctx* c, const void* q, const void* k_cache, c
   DeviceGuard guard(c->device);
   if (!guard.ok) return ECOSERVE_EHIP;
   hipStream_t s = (hipStream_t)stream;
-  const AttnArgs a = make_args(c, q, k_cache, v_cache, block_table, bt_stride, out, lse, B);
+  const AttnArgs a = make_args(c, q, q_row_stride, k_cache, v_cache, block_table, bt_stride, out, lse, B);
   ProfileScope prof(c, ECOSERVE_KERNEL_PREFILL, s);
   hipError_t e;
   if (use_mfma(c)) {
@@ -331,7 +359,17 @@ int ecoserve_attn_prefill(ecoserve_ctx* c, const void* q, const void* k_cache, c
 int ecoserve_attn_decode(ecoserve_ctx* c, const void* q, const void* k_cache, const void* v_cache,
                          const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len, void* out,
                          float* lse, int32_t B, int32_t max_ctx_len, void* stream) {
+  if (!c) return ECOSERVE_EINVAL;
+  return ecoserve_attn_decode_strided(c, q, (int64_t)c->lay.num_q_heads * c->lay.head_dim, k_cache, v_cache,
+                                      block_table, bt_stride, ctx_len, out, lse, B, max_ctx_len, stream);
+}
+
+int ecoserve_attn_decode_strided(ecoserve_ctx* c, const void* q, int64_t q_row_stride, const void* k_cache,
+                                 const void* v_cache, const int32_t* block_table, int32_t bt_stride,
+                                 const int32_t* ctx_len, void* out, float* lse, int32_t B, int32_t max_ctx_len,
+                                 void* stream) {
   if (!c || B < 0 || max_ctx_len < 0) return ECOSERVE_EINVAL;
+  if (!stride_ok(c, q_row_stride, c->lay.num_q_heads)) return ECOSERVE_EINVAL;
   if (B == 0) return ECOSERVE_OK;
   if (!q || !k_cache || !v_cache || !block_table || !ctx_len || !out) return ECOSERVE_EINVAL;
   if (B > c->max_batch || bt_stride <= 0 || max_ctx_len < 1) return ECOSERVE_EINVAL;
@@ -343,7 +381,7 @@ int ecoserve_attn_decode(ecoserve_ctx* c, const void* q, const void* k_cache, co
   DeviceGuard guard(c->device);
   if (!guard.ok) return ECOSERVE_EHIP;
   hipStream_t s = (hipStream_t)stream;
-  const AttnArgs a = make_args(c, q, k_cache, v_cache, block_table, bt_stride, out, lse, B);
+  const AttnArgs a = make_args(c, q, q_row_stride, k_cache, v_cache, block_table, bt_stride, out, lse, B);
   hipError_t e;
   if (use_mfma(c)) {
     const int n_wgs = c->num_cu * kDecodeWgsPerCu;

@@ -168,7 +168,7 @@ struct Chunking {
 constexpr int kMetaPre = 18;  // ws_meta: [0..7] c, [8..16] cum, then the batch prefix sums
 
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
-    const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
+    const uint16_t* __restrict__ q, int q_row_stride, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
     int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, const float* __restrict__ share_in,
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
   };
   // B operand of S^T: Q^T[d][head], heads beyond the group are zero columns
   auto load_q = [&](bf16x8 (&qf)[4], const Piece& p) {
-    const uint16_t* qrow = q + ((size_t)p.b * Hq + (size_t)p.g * G + col) * 128;
+    const uint16_t* qrow = q + (size_t)p.b * q_row_stride + ((size_t)p.g * G + col) * 128;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -449,7 +449,7 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   if (n_wg % 8 != 0) share_in = nullptr;  // the rounds of 8 workgroups would not line up with the XCDs
   if (!share_in) ws_wave = nullptr;
   hipLaunchKernelGGL(decode_mfma_kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q,
-                     (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
+                     a.q_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
                      (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out, xcd_speed, ws_wave, a.B, a.Hq,
                      a.Hkv, G, a.scale_log2e);
   return hipGetLastError();

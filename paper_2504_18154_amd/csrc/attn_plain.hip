@@ -80,7 +80,8 @@ __device__ __forceinline__ int find_seq(const int32_t* __restrict__ cu_q, int B,
 
 // grid (T, Hq), 64 threads: query token t, head h; attends keys 0..ctx_before+i.
 template <typename E>
-__global__ __launch_bounds__(64) void prefill_plain_kernel(const E* __restrict__ q, const E* __restrict__ k_cache,
+__global__ __launch_bounds__(64) void prefill_plain_kernel(const E* __restrict__ q, int q_row_stride,
+                                                           const E* __restrict__ k_cache,
                                                            const E* __restrict__ v_cache,
                                                            const int32_t* __restrict__ cu_q,
                                                            const int32_t* __restrict__ ctx_before,
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(64) void prefill_plain_kernel(const E* __restrict__
   const int b = find_seq(cu_q, B, t);
   const int p = ctx_before[b] + (t - cu_q[b]);
   const int g = h / (Hq / Hkv);
-  load_query(sq, q + ((size_t)t * Hq + h) * D, D);
+  load_query(sq, q + (size_t)t * q_row_stride + h * D, D);
   float m, l, o[kMaxD / 64];
   plain_attend<E>(sq, sp, k_cache, v_cache, block_table + (size_t)b * bt_stride, g, Hkv, D, 0, p + 1, scale_log2e,
                   m, l, o);
@@ -108,7 +109,8 @@ __global__ __launch_bounds__(64) void prefill_plain_kernel(const E* __restrict__
 
 // grid (n_split_max, Hq, B), 64 threads: one context slice of one (sequence, head).
 template <typename E>
-__global__ __launch_bounds__(64) void decode_plain_kernel(const E* __restrict__ q, const E* __restrict__ k_cache,
+__global__ __launch_bounds__(64) void decode_plain_kernel(const E* __restrict__ q, int q_row_stride,
+                                                          const E* __restrict__ k_cache,
                                                           const E* __restrict__ v_cache,
                                                           const int32_t* __restrict__ block_table, int bt_stride,
                                                           const int32_t* __restrict__ ctx_len, E* __restrict__ out,
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(64) void decode_plain_kernel(const E* __restrict__ 
   const int n_split = (L + split_tokens - 1) / split_tokens;
   if (sp_idx >= n_split) return;
   const int g = h / (Hq / Hkv);
-  load_query(sq, q + ((size_t)b * Hq + h) * D, D);
+  load_query(sq, q + (size_t)b * q_row_stride + h * D, D);
   const int t0 = sp_idx * split_tokens, t1 = min(L, t0 + split_tokens);
   float m, l, o[kMaxD / 64];
   plain_attend<E>(sq, sp, k_cache, v_cache, block_table + (size_t)b * bt_stride, g, Hkv, D, t0, t1, scale_log2e, m, l,
@@ -185,11 +187,12 @@ hipError_t launch_prefill_plain(const AttnArgs& a, const int32_t* cu_q, const in
                                 hipStream_t s) {
   dim3 grid((unsigned)T, (unsigned)a.Hq);
   if (a.dtype == ECOSERVE_BF16) {
-    hipLaunchKernelGGL(prefill_plain_kernel<uint16_t>, grid, dim3(64), 0, s, (const uint16_t*)a.q,
+    hipLaunchKernelGGL(prefill_plain_kernel<uint16_t>, grid, dim3(64), 0, s, (const uint16_t*)a.q, a.q_row_stride,
                        (const uint16_t*)a.k_cache, (const uint16_t*)a.v_cache, cu_q, ctx_before, a.block_table,
                        a.bt_stride, (uint16_t*)a.out, a.lse, a.B, a.Hq, a.Hkv, a.D, a.scale_log2e);
   } else {
-    hipLaunchKernelGGL(prefill_plain_kernel<float>, grid, dim3(64), 0, s, (const float*)a.q, (const float*)a.k_cache,
+    hipLaunchKernelGGL(prefill_plain_kernel<float>, grid, dim3(64), 0, s, (const float*)a.q, a.q_row_stride,
+                       (const float*)a.k_cache,
                        (const float*)a.v_cache, cu_q, ctx_before, a.block_table, a.bt_stride, (float*)a.out, a.lse,
                        a.B, a.Hq, a.Hkv, a.D, a.scale_log2e);
   }
@@ -200,12 +203,13 @@ hipError_t launch_decode_plain(const AttnArgs& a, const int32_t* ctx_len, int32_
                                float* ws_acc, float* ws_ml, int32_t ws_splits, hipStream_t s) {
   dim3 grid((unsigned)n_split_max, (unsigned)a.Hq, (unsigned)a.B);
   if (a.dtype == ECOSERVE_BF16) {
-    hipLaunchKernelGGL(decode_plain_kernel<uint16_t>, grid, dim3(64), 0, s, (const uint16_t*)a.q,
+    hipLaunchKernelGGL(decode_plain_kernel<uint16_t>, grid, dim3(64), 0, s, (const uint16_t*)a.q, a.q_row_stride,
                        (const uint16_t*)a.k_cache, (const uint16_t*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
                        (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_splits, split_tokens, a.Hq, a.Hkv, a.D,
                        a.scale_log2e);
   } else {
-    hipLaunchKernelGGL(decode_plain_kernel<float>, grid, dim3(64), 0, s, (const float*)a.q, (const float*)a.k_cache,
+    hipLaunchKernelGGL(decode_plain_kernel<float>, grid, dim3(64), 0, s, (const float*)a.q, a.q_row_stride,
+                       (const float*)a.k_cache,
                        (const float*)a.v_cache, a.block_table, a.bt_stride, ctx_len, (float*)a.out, a.lse, ws_acc,
                        ws_ml, ws_splits, split_tokens, a.Hq, a.Hkv, a.D, a.scale_log2e);
   }

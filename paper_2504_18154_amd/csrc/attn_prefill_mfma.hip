@@ -315,9 +315,9 @@ __device__ __forceinline__ Item describe(int rec, int g, int h, const int32_t* _
 }
 
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
-    const uint16_t* __restrict__ q, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
-    const int32_t* __restrict__ block_table, int bt_stride, uint16_t* __restrict__ out, float* __restrict__ lse,
-    int32_t* __restrict__ plan, int parity, int Hq, int Hkv, int G, Divisor div_heads, Divisor div_hkv,
+    const uint16_t* __restrict__ q, int q_row_stride, const char* __restrict__ k_cache,
+    const char* __restrict__ v_cache, const int32_t* __restrict__ block_table, int bt_stride,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int32_t* __restrict__ plan, int parity, int Hq, int Hkv, int G, Divisor div_heads, Divisor div_hkv,
     float scale_log2e) {
   __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes + 16];
   char* const kbufs = smem;
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   bf16x8 qf[8];
   auto load_q = [&](const Item& t) {
     const int r = t.q0 + wave * 32 + col;
-    const uint16_t* qrow = q + ((size_t)(t.tok0 + r) * Hq + t.h) * 128 + half * 8;
+    const uint16_t* qrow = q + (size_t)(t.tok0 + r) * q_row_stride + t.h * 128 + half * 8;
     const bool ok = r < t.S;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -696,7 +696,7 @@ hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, cu_q, ctx_before, a.block_table,
                        a.bt_stride, a.B, (int)n_wg, (int)max_tiles, ws_plan);
   hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q,
-                     (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
+                     a.q_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
                      a.lse, ws_plan, parity, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)),
                      make_divisor((uint32_t)a.Hkv),
                      a.scale_log2e);

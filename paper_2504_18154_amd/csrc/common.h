@@ -107,6 +107,7 @@ namespace eco {
 // Arguments common to the attention launchers.
 struct AttnArgs {
   const void* q;
+  int32_t q_row_stride;  // elements between the query rows of consecutive tokens (>= Hq * D)
   const void* k_cache;
   const void* v_cache;
   const int32_t* block_table;
@@ -120,8 +121,9 @@ struct AttnArgs {
 };
 
 // kv_append.hip
+// (new_row_stride: elements between the K rows, and between the V rows, of consecutive tokens)
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
-                            const void* v_new, const int32_t* cu_q, const int32_t* ctx_before,
+                            const void* v_new, int32_t new_row_stride, const int32_t* cu_q, const int32_t* ctx_before,
                             const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
                             int32_t max_new_len, hipStream_t s);
 

@@ -5,7 +5,9 @@
 // absolute position p = ctx_before[b] + i: block block_table[b][p / 16], slot p % 16.
 // Pure integer indexing and byte copies, so the result is bit-exact.
 //
-// Source rows are [T][Hkv][D]; destination is the library's block layout
+// Source rows are [Hkv][D] per token, consecutive tokens `new_row_stride` elements apart (Hkv * D for a
+// packed [T][Hkv][D] array, more when K and V sit inside a wider row such as a fused projection output,
+// Eq. 1); destination is the library's block layout
 //   K: [blk][Hkv][D/x][16 slots][x]   (x = elements per 16 bytes)
 //   V: [blk][Hkv][D][16 slots]
 // One workgroup fills one destination block for up to four adjacent K/V heads: up to 16 token
@@ -74,7 +76,7 @@ __device__ __forceinline__ void scan_touched_blocks(int* pre, int* tok, int* cbs
 template <typename E, int HPW>
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
                                                                     const E* __restrict__ k_new,
-                                                                    const E* __restrict__ v_new,
+                                                                    const E* __restrict__ v_new, int new_row_stride,
                                                                     const int32_t* __restrict__ cu_q,
                                                                     const int32_t* __restrict__ ctx_before,
                                                                     const int32_t* __restrict__ block_table,
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
   for (int u = tid; u < 16 * upr; u += kAppendThreads) {
     const int slot = u & 15, c = u >> 4;
     if (slot >= lo && slot < hi) {
-      const E* src = k_new + ((size_t)(t_slot0 + slot) * Hkv + g0) * D + c * X;
+      const E* src = k_new + (size_t)(t_slot0 + slot) * new_row_stride + g0 * D + c * X;
       u4 val[HPW];
 #pragma unroll
       for (int h = 0; h < HPW; ++h) val[h] = *reinterpret_cast<const u4*>(src + (size_t)h * D);
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
   for (int u = tid; u < 16 * upr; u += kAppendThreads) {
     const int slot = u / upr, c = u % upr;
     if (slot >= lo && slot < hi) {
-      const E* src = v_new + ((size_t)(t_slot0 + slot) * Hkv + g0) * D + c * X;
+      const E* src = v_new + (size_t)(t_slot0 + slot) * new_row_stride + g0 * D + c * X;
       u4 val[HPW];
 #pragma unroll
       for (int h = 0; h < HPW; ++h) val[h] = *reinterpret_cast<const u4*>(src + (size_t)h * D);
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(E* __restrict
 template <typename E>
 __global__ __launch_bounds__(kAppendThreads) void kv_append_one_kernel(E* __restrict__ k_cache, E* __restrict__ v_cache,
                                                                         const E* __restrict__ k_new,
-                                                                        const E* __restrict__ v_new,
+                                                                        const E* __restrict__ v_new, int new_row_stride,
                                                                         const int32_t* __restrict__ cu_q,
                                                                         const int32_t* __restrict__ ctx_before,
                                                                         const int32_t* __restrict__ block_table,
@@ -175,11 +177,11 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_one_kernel(E* __rest
   if (cu_q[b + 1] - tok <= 0) return;
   const int p = ctx_before[b], slot = p & 15;
   const int64_t blk = block_table[(size_t)b * bt_stride + (p >> 4)];
-  const E* ksrc = k_new + ((size_t)tok * Hkv + g) * D;
+  const E* ksrc = k_new + (size_t)tok * new_row_stride + g * D;
   E* kdst = k_cache + ((size_t)blk * Hkv + g) * 16 * D + (size_t)slot * X;
   for (int c = lane; c < D / X; c += 64)
     *reinterpret_cast<u4*>(kdst + (size_t)c * 16 * X) = *reinterpret_cast<const u4*>(ksrc + c * X);
-  const E* vsrc = v_new + ((size_t)tok * Hkv + g) * D;
+  const E* vsrc = v_new + (size_t)tok * new_row_stride + g * D;
   E* vdst = v_cache + ((size_t)blk * Hkv + g) * D * 16 + slot;
   for (int d = lane; d < D; d += 64) vdst[(size_t)d * 16] = vsrc[d];
 }
@@ -193,7 +195,7 @@ static size_t append_lds_bytes(int B, int D, int hpw) {
 
 template <typename E, int HPW>
 static void launch_tiled(const ecoserve_layout& L, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
-                         const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
+                         int32_t new_row_stride, const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
                          int32_t bt_stride, int32_t B, int32_t T, hipStream_t s) {
   // a sequence with S new tokens touches at most S/16 + 2 blocks (ragged at both ends), and none if S == 0
   const int64_t max_units = (int64_t)T / 16 + 2 * (int64_t)(B < T ? B : T);
@@ -204,39 +206,39 @@ static void launch_tiled(const ecoserve_layout& L, void* k_cache, void* v_cache,
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&kv_append_kernel<E, HPW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL((kv_append_kernel<E, HPW>), grid, dim3(kAppendThreads), lds, s, (E*)k_cache, (E*)v_cache,
-                     (const E*)k_new, (const E*)v_new, cu_q, ctx_before, block_table, bt_stride, B, L.num_kv_heads,
-                     L.head_dim);
+                     (const E*)k_new, (const E*)v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B,
+                     L.num_kv_heads, L.head_dim);
 }
 
 template <typename E>
 static void launch_typed(const ecoserve_layout& L, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
-                         const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
+                         int32_t new_row_stride, const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
                          int32_t bt_stride, int32_t B, int32_t T, int32_t max_new_len, hipStream_t s) {
   if (max_new_len <= 1) {
     const int per_wg = kAppendThreads / 64;
     const dim3 grid((unsigned)(((int64_t)B * L.num_kv_heads + per_wg - 1) / per_wg));
     hipLaunchKernelGGL((kv_append_one_kernel<E>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
-                       (const E*)k_new, (const E*)v_new, cu_q, ctx_before, block_table, bt_stride, B,
+                       (const E*)k_new, (const E*)v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B,
                        L.num_kv_heads, L.head_dim);
   } else if (L.num_kv_heads % 4 == 0) {
-    launch_tiled<E, 4>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T, s);
+    launch_tiled<E, 4>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T, s);
   } else if (L.num_kv_heads % 2 == 0) {
-    launch_tiled<E, 2>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T, s);
+    launch_tiled<E, 2>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T, s);
   } else {
-    launch_tiled<E, 1>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T, s);
+    launch_tiled<E, 1>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T, s);
   }
 }
 
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
-                            const void* v_new, const int32_t* cu_q, const int32_t* ctx_before,
-                            const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
-                            int32_t max_new_len, hipStream_t s) {
+                            const void* v_new, int32_t new_row_stride, const int32_t* cu_q,
+                            const int32_t* ctx_before, const int32_t* block_table, int32_t bt_stride, int32_t B,
+                            int32_t T, int32_t max_new_len, hipStream_t s) {
   const ecoserve_layout& L = ctx->lay;
   if (L.dtype == ECOSERVE_BF16)
-    launch_typed<uint16_t>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T,
+    launch_typed<uint16_t>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T,
                            max_new_len, s);
   else
-    launch_typed<float>(L, k_cache, v_cache, k_new, v_new, cu_q, ctx_before, block_table, bt_stride, B, T,
+    launch_typed<float>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T,
                         max_new_len, s);
   return hipGetLastError();
 }

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import oracle as orc
 from paper_2504_18154_amd import workloads as wl
 from tests.parity_util import Layer, compare, compare_lse, dev_i32, say
 
@@ -526,6 +527,81 @@ def test_empty_batches_and_host_side_errors():
     dup = pb.block_table.copy(); dup[2, 0] = dup[0, 0]
     assert c.debug_validate(cu, total, dev_i32(dup)) == binding.ECONTENT
     assert c.debug_validate(None, dev_i32([40, 0, 7]), bt) == binding.ECONTENT   # decode needs ctx_len >= 1
+    layer.close()
+
+
+@pytest.mark.parametrize("dtype,pad", [("bf16", 0), ("f32", 0), ("bf16", 24)])
+def test_fused_projection_rows_are_read_in_place(dtype, pad):
+    """Q, K and V as slices of one row [Hq + 2 Hkv (+ padding)][D] per token, the shape in which a fused
+    projection (Eq. 1) leaves them: the strided calls read them where they are.  Append bit-exact, prefill
+    and decode against the oracle and bit-identical to the packed calls on copies of the same slices; a
+    prefix chunk first so that the second append starts inside a block."""
+    from paper_2504_18154_amd import binding
+    model = M30 if dtype == "bf16" else wl.ModelShape("small-f32", 4, 2, 64, 1, "f32")
+    Hq, Hkv, D = model.Hq, model.Hkv, model.D
+    first, second = [70, 0, 203, 5], [130, 257, 1, 64]
+    say(f"{dtype} fused rows, {pad} padding elements per row: prefix {first} + new {second}")
+    pb, layer = _mk(model, [a + b + 1 for a, b in zip(first, second)], seed=61)
+    cu1, cu2 = wl.cu_from_lengths(first), wl.cu_from_lengths(second)
+    cb = np.asarray(first, dtype=np.int32)
+    table = dev_i32(pb.block_table)
+
+    def fused(T, seed):
+        rows = wl.randn((T, (Hq + 2 * Hkv) * D + pad), dtype, seed, device="cuda")
+        body = rows[:, :(Hq + 2 * Hkv) * D].unflatten(1, (Hq + 2 * Hkv, D))
+        return body[:, :Hq], body[:, Hq:Hq + Hkv], body[:, Hq + Hkv:]
+
+    _, k1, v1 = fused(int(cu1[-1]), 610)
+    layer.ctx.kv_append_strided(layer.kc, layer.vc, k1, v1, dev_i32(cu1), dev_i32(np.zeros(4, np.int32)), table)
+
+    def orc_append(k, v, cu, before):
+        orc.kv_append(layer.shape, layer.okc, layer.ovc, wl.to_bits(k), wl.to_bits(v), cu, before, pb.block_table)
+
+    orc_append(k1, v1, cu1, np.zeros(4, np.int32))
+    q2, k2, v2 = fused(int(cu2[-1]), 620)
+    assert not q2.is_contiguous() and not k2.is_contiguous()
+    layer.ctx.kv_append_strided(layer.kc, layer.vc, k2, v2, dev_i32(cu2), dev_i32(cb), table)
+    orc_append(k2, v2, cu2, cb)
+    layer.assert_cache_bit_exact()
+
+    out = torch.full((q2.shape[0], Hq, D), float("nan"), dtype=q2.dtype, device="cuda")
+    lse = torch.full((q2.shape[0], Hq), float("nan"), dtype=torch.float32, device="cuda")
+    layer.ctx.attn_prefill_strided(q2, layer.kc, layer.vc, dev_i32(cu2), dev_i32(cb), table, out, lse,
+                                   max_q_len=max(second))
+    ref, ref_lse = layer.prefill_oracle(q2, cu2, cb, pb.block_table)
+    compare("prefill on fused rows", out, ref, dtype)
+    compare_lse("prefill on fused rows", lse, ref_lse, dtype)
+    packed, _ = layer.prefill_gpu(q2.contiguous(), cu2, cb, pb.block_table)
+    assert torch.equal(out.view(torch.uint8), packed.view(torch.uint8)), "strided and packed prefill differ"
+
+    ctx = cb + np.asarray(second, dtype=np.int32)
+    qd, kd, vd = fused(4, 630)
+    layer.ctx.kv_append_strided(layer.kc, layer.vc, kd, vd, dev_i32(wl.cu_from_lengths([1] * 4)), dev_i32(ctx), table,
+                                max_new_len=1)
+    orc_append(kd, vd, wl.cu_from_lengths([1] * 4), ctx)
+    layer.assert_cache_bit_exact()
+    ctx = ctx + 1
+    out = torch.full((4, Hq, D), float("nan"), dtype=qd.dtype, device="cuda")
+    lse = torch.full((4, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    layer.ctx.attn_decode_strided(qd, layer.kc, layer.vc, table, dev_i32(ctx), out, int(ctx.max()), lse)
+    ref, ref_lse = layer.decode_oracle(qd, pb.block_table, ctx)
+    compare("decode on fused rows", out, ref, dtype)
+    compare_lse("decode on fused rows", lse, ref_lse, dtype)
+    packed, _ = layer.decode_gpu(qd.contiguous(), pb.block_table, ctx)
+    assert torch.equal(out.view(torch.uint8), packed.view(torch.uint8)), "strided and packed decode differ"
+
+    # strides the library must refuse: shorter than a packed row, not a multiple of 16 bytes, 2^31 or more
+    lib, h, vp = binding._lib, layer.ctx._h, binding._ptr
+    for bad in (Hkv * D - 8, Hkv * D + 1, 1 << 31):
+        st = lib.ecoserve_kv_append_strided(h, vp(layer.kc), vp(layer.vc), vp(kd), vp(vd), bad,
+                                            vp(dev_i32(wl.cu_from_lengths([1] * 4))), vp(dev_i32(ctx)), vp(table),
+                                            pb.block_table.shape[1], 4, 4, 1, None)
+        assert st == binding.EINVAL, bad
+    for bad in (Hq * D - 8, Hq * D + 1, 1 << 31):
+        st = lib.ecoserve_attn_decode_strided(h, vp(qd), bad, vp(layer.kc), vp(layer.vc), vp(table),
+                                              pb.block_table.shape[1], vp(dev_i32(ctx)), vp(out), None, 4,
+                                              int(ctx.max()), None)
+        assert st == binding.EINVAL, bad
     layer.close()
 
 
