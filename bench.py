@@ -18,8 +18,14 @@ It prints ONE JSON line.  `value` is the decode phase's algorithmic HBM traffic 
 the headline metric; the prefill phase's causal TFLOP/s and the append rates ride along.
 `roofline` is for the dominant kernel (decode partial attention): algorithmic bytes per
 launch / its average launch duration, measured with HIP events recorded by the library on
-the launch stream around every launch inside the timed region.  `cpu_baseline` is the fp64
+the launch stream around every 7th launch inside the timed region.  `cpu_baseline` is the fp64
 oracle on the host cores, on one layer of the decode batch.
+
+    python bench.py --sweep
+
+times the kernels alone on the other batch shapes (the 70B-scale decode and phase-switch
+configurations, a multi-head model, longer contexts, uniform prompt lengths) over a few layer
+caches each and prints one JSON line {"sweep": [...]}: the source of the table in the benchmark spec.
 """
 from __future__ import annotations
 
@@ -32,6 +38,111 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+
+
+def sweep() -> int:
+    """Kernel time and rate on other batch shapes, a few layer caches each, all launches bracketed."""
+    import numpy as np
+    import torch
+
+    from paper_2504_18154_amd import accounting as acc
+    from paper_2504_18154_amd import binding, build
+    from paper_2504_18154_amd import workloads as wl
+
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(0)
+    i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=dev)
+    rows = []
+
+    def pools(n_elems, layers, seed):
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        mk = lambda: torch.randn(n_elems, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        return [(mk(), mk()) for _ in range(layers)]
+
+    def run_passes(ctx, one_pass, warm_ms=60.0, timed_ms=60.0):
+        """Untimed passes until the chip has been busy for warm_ms (clocks settle), then bracketed passes."""
+        for phase_ms, bracket in ((warm_ms, False), (timed_ms, True)):
+            if bracket:
+                ctx.set_option(binding.OPT_PROFILE, 1)
+                ctx.profile_reset()
+            t0, n = time.perf_counter(), 0
+            while n < 3 or (time.perf_counter() - t0) * 1e3 < phase_ms:
+                one_pass()
+                torch.cuda.synchronize()
+                n += 1
+
+    def decode(name, db, layers=4):
+        m = db.model
+        ctx = binding.Context(m.Hq, m.Hkv, m.D, db.num_blocks, "bf16", db.B, db.block_table.shape[1])
+        ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
+        caches = pools(db.num_blocks * m.Hkv * m.bs * m.D, layers, db.seed)
+        q = wl.randn((db.B, m.Hq, m.D), "bf16", db.seed + 3, device=dev)
+        out = torch.empty_like(q)
+        bt, cl = i32(db.block_table), i32(db.ctx_len)
+
+        def one_pass():
+            for kc, vc in caches:
+                ctx.attn_decode(q, kc, vc, bt, cl, out, db.max_ctx_len)
+
+        run_passes(ctx, one_pass)
+        ms, n = ctx.profile_read(binding.KERNEL_DECODE)
+        by = acc.decode_bytes(db.ctx_len, m.Hq, m.Hkv, m.D, m.bs)
+        rate = by / (ms / n * 1e-3) / 1e9
+        rows.append({"workload": name, "kernel": "decode_mfma_kernel", "avg_launch_us": ms / n * 1e3, "launches": n,
+                     "algorithmic_bytes_per_launch": by, "GBps": rate, "frac_of_hbm_peak": rate / acc.PEAK_HBM_GBPS})
+        ctx.close()
+
+    def prefill(name, m, q_len, layers=2):
+        pb = wl.prefill_batch(m, q_len, 3)
+        ctx = binding.Context(m.Hq, m.Hkv, m.D, pb.num_blocks, "bf16", pb.B, pb.block_table.shape[1])
+        ctx.set_option(binding.OPT_PREFILL_REUSE_PLAN, 1)
+        q = wl.randn((pb.T, m.Hq, m.D), "bf16", 11, device=dev)
+        k = wl.randn((pb.T, m.Hkv, m.D), "bf16", 12, device=dev)
+        v = wl.randn((pb.T, m.Hkv, m.D), "bf16", 13, device=dev)
+        out = torch.empty_like(q)
+        cu, cb, bt = i32(pb.cu_q), i32(pb.ctx_before), i32(pb.block_table)
+        caches = [ctx.new_cache(fill_bits=0) for _ in range(layers)]
+
+        def one_pass():
+            ctx.set_option(binding.OPT_PREFILL_REUSE_PLAN, 1)   # one list of query tiles per pass over the layers
+            for kc, vc in caches:
+                ctx.kv_append(kc, vc, k, v, cu, cb, bt, max_new_len=pb.max_q_len)
+                ctx.attn_prefill(q, kc, vc, cu, cb, bt, out, max_q_len=pb.max_q_len)
+
+        run_passes(ctx, one_pass)
+        ms, n = ctx.profile_read(binding.KERNEL_PREFILL)
+        ams, an = ctx.profile_read(binding.KERNEL_APPEND)
+        fl = acc.prefill_flops_causal(pb.q_len, m.Hq, m.D)
+        tf = fl / (ms / n * 1e-3) / 1e12
+        ab = acc.append_bytes(pb.T, m.Hkv, m.D)
+        rows.append({"workload": name, "kernel": "prefill_mfma_kernel", "avg_launch_us": ms / n * 1e3, "launches": n,
+                     "algorithmic_flops_per_launch": fl, "TFLOPs": tf, "frac_of_bf16_peak": tf / acc.PEAK_BF16_TFLOPS,
+                     "append_us": ams / an * 1e3, "append_GBps": ab / (ams / an * 1e-3) / 1e9})
+        ctx.close()
+
+    decode("30B decode: 128 seqs, ctx U[512,4096] (BASELINE config 1)", wl.config2_decode_30b())
+    decode("70B decode: 256 seqs, ctx U[1024,4096], 64 q heads (BASELINE config 3)", wl.config4_decode_70b())
+    resident, new, table, nb = wl.config5_switch_70b()
+    decode("70B phase switch, decode side: 192 resident + 8 new x 8192 (BASELINE config 4)",
+           wl.DecodeBatch(wl.M70B, np.concatenate([resident, new]).astype(np.int32), table, nb, 0), layers=2)
+    decode("30B, 128 seqs, every context 8192", wl.decode_batch(wl.M30B, 128, 8192, 8192, 5))
+    decode("multi-head model (52 q = 52 kv heads), 128 seqs, ctx U[512,4096]",
+           wl.decode_batch(wl.M30B_MHA, 128, 512, 4096, 7), layers=2)
+    decode("30B, 16 seqs, ctx U[512,4096] (small batch)", wl.decode_batch(wl.M30B, 16, 512, 4096, 6))
+    prefill("30B prefill: 16 prompts lognormal in [128,4096] (BASELINE config 2)", wl.M30B,
+            wl.config3_prefill_30b().q_len)
+    prefill("70B phase switch, prefill side: 8 x 8192, 64 q heads (BASELINE config 4)", wl.M70B, [8192] * 8)
+    prefill("30B, 16 x 1024", wl.M30B, [1024] * 16)
+    prefill("30B, 64 x 256", wl.M30B, [256] * 64)
+    prefill("30B, 4 x 4096", wl.M30B, [4096] * 4)
+    prefill("multi-head model (52/52), 16 x 1024", wl.M30B_MHA, [1024] * 16)
+    print(json.dumps({"sweep": rows, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "note": "kernel time alone from HIP events around every launch; decode with per-XCD shares"}))
+    return 0
 
 
 def main() -> int:
@@ -57,6 +168,8 @@ def main() -> int:
                          "per launch delays the stream by several microseconds per layer; 1 = every launch)")
     ap.add_argument("--no-probes", action="store_true",
                     help="skip the two machine-ceiling probes (streaming read, matrix-core loop) after the timed region")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the kernels alone on the other batch shapes and print {\"sweep\": [...]} instead")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -65,6 +178,8 @@ def main() -> int:
               "run with --gpus 1", file=sys.stderr)
         return 2
 
+    if args.sweep:
+        return sweep()
     if args.fused_qkv and args.prefill_chunk:
         print("bench.py: --fused-qkv and --prefill-chunk are separate experiments; give one of them", file=sys.stderr)
         return 2
