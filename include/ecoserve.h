@@ -29,6 +29,12 @@
  *   - Calls that share a context must be issued on one stream (or be ordered
  *     by the caller): they share the context's workspace (split-context partial
  *     states of decode, the query-tile list of prefill).
+ *   - With the default options the hot calls may be recorded into a HIP graph
+ *     (they neither allocate nor synchronise, and record no memset nodes).
+ *     Options whose state advances on the host from call to call
+ *     (ECOSERVE_OPT_PROFILE, ECOSERVE_OPT_DECODE_ADAPTIVE,
+ *     ECOSERVE_OPT_PREFILL_REUSE_PLAN) are for eager calls: a recorded launch
+ *     replays the arguments it was recorded with.
  *
  * Notation (Table 1 of the paper, extended): B sequences in the batch, Hq
  * query heads (M in the paper), Hkv key/value heads, G = Hq/Hkv, D per-head

@@ -605,6 +605,66 @@ def test_fused_projection_rows_are_read_in_place(dtype, pad):
     layer.close()
 
 
+def test_hot_calls_can_be_captured_in_a_hip_graph():
+    """One decode step of three layers (append one token, decode) and one prefill call recorded into a HIP
+    graph and replayed three times with new input contents and the program's own eager work in between:
+    every replay must give exactly what the eager calls give on the same inputs.  The hot calls neither
+    allocate nor synchronise, so a capturing stream can take them (default options: equal decode shares, a
+    tile list per prefill call)."""
+    model = M30
+    layers = 3
+    lens = [700, 33, 1500, 64, 257]
+    say("HIP graph capture of append + decode (3 layers) and of prefill")
+    pb = wl.prefill_batch(model, [n + 1 for n in lens], 71)
+    Ls = [Layer(model, pb.num_blocks, pb.B, pb.block_table.shape[1], oracle_cache=False) for _ in range(layers)]
+    table = dev_i32(pb.block_table)
+    cu = dev_i32(wl.cu_from_lengths(lens))
+    zero = dev_i32(np.zeros(pb.B))
+    for i, L in enumerate(Ls):
+        _, k, v = _qkv(model, sum(lens), 710 + 10 * i)
+        L.ctx.kv_append(L.kc, L.vc, k.cuda(), v.cuda(), cu, zero, table)
+    ones = dev_i32(wl.cu_from_lengths([1] * pb.B))
+    before, ctx = dev_i32(np.asarray(lens)), dev_i32(np.asarray(lens) + 1)
+    B, T = pb.B, sum(lens)
+    q = torch.empty((B, model.Hq, model.D), dtype=torch.bfloat16, device="cuda")
+    kn, vn = (torch.empty((B, model.Hkv, model.D), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    qp = torch.empty((T, model.Hq, model.D), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty((layers, B, model.Hq, model.D), dtype=torch.bfloat16, device="cuda")
+    outp = torch.empty_like(qp)
+
+    def work():
+        for i, L in enumerate(Ls):
+            L.ctx.kv_append(L.kc, L.vc, kn, vn, ones, before, table, max_new_len=1)
+            L.ctx.attn_decode(q, L.kc, L.vc, table, ctx, out[i], max(lens) + 1)
+        Ls[0].ctx.attn_prefill(qp, Ls[0].kc, Ls[0].vc, cu, zero, table, outp, max_q_len=max(lens))
+
+    def new_inputs(seed):
+        q.copy_(wl.randn(q.shape, "bf16", seed, device="cuda"))
+        kn.copy_(wl.randn(kn.shape, "bf16", seed + 1, device="cuda"))
+        vn.copy_(wl.randn(vn.shape, "bf16", seed + 2, device="cuda"))
+        qp.copy_(wl.randn(qp.shape, "bf16", seed + 3, device="cuda"))
+
+    new_inputs(720)
+    work()                      # warm: nothing is created lazily inside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        work()
+    for r in range(3):
+        new_inputs(730 + 10 * r)
+        work()
+        torch.cuda.synchronize()
+        want, wantp = out.clone(), outp.clone()
+        out.fill_(float("nan"))
+        outp.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), f"decode: replay {r} differs from eager"
+        assert torch.equal(outp.view(torch.int16), wantp.view(torch.int16)), f"prefill: replay {r} differs from eager"
+    for L in Ls:
+        L.close()
+
+
 def test_machine_ceiling_probes_report_plausible_rates():
     """The two measurement helpers run, return rates of the right order for this class of device (between
     a quarter of and the whole published peak: 8 TB/s, 2.5 PFLOP/s) and reject bad arguments."""
