@@ -133,6 +133,9 @@ def sweep() -> int:
     decode("multi-head model (52 q = 52 kv heads), 128 seqs, ctx U[512,4096]",
            wl.decode_batch(wl.M30B_MHA, 128, 512, 4096, 7), layers=2)
     decode("30B, 16 seqs, ctx U[512,4096] (small batch)", wl.decode_batch(wl.M30B, 16, 512, 4096, 6))
+    decode("30B, 512 seqs, contexts shaped like ShareGPT (Table 4)", wl.table4_decode_batch(wl.M30B, "sharegpt", 512, 21))
+    decode("30B, 1024 seqs, contexts shaped like Alpaca (Table 4)", wl.table4_decode_batch(wl.M30B, "alpaca", 1024, 22))
+    decode("30B, 64 seqs, contexts shaped like LongBench (Table 4)", wl.table4_decode_batch(wl.M30B, "longbench", 64, 23))
     prefill("30B prefill: 16 prompts lognormal in [128,4096] (BASELINE config 2)", wl.M30B,
             wl.config3_prefill_30b().q_len)
     prefill("70B phase switch, prefill side: 8 x 8192, 64 q heads (BASELINE config 4)", wl.M70B, [8192] * 8)
@@ -140,6 +143,9 @@ def sweep() -> int:
     prefill("30B, 64 x 256", wl.M30B, [256] * 64)
     prefill("30B, 4 x 4096", wl.M30B, [4096] * 4)
     prefill("multi-head model (52/52), 16 x 1024", wl.M30B_MHA, [1024] * 16)
+    prefill("30B, 64 prompts shaped like ShareGPT (Table 4)", wl.M30B, wl.table4_lengths("sharegpt", wl.rng_for(31), 64)[0])
+    prefill("30B, 512 prompts shaped like Alpaca (Table 4)", wl.M30B, wl.table4_lengths("alpaca", wl.rng_for(32), 512)[0])
+    prefill("30B, 8 prompts shaped like LongBench (Table 4)", wl.M30B, wl.table4_lengths("longbench", wl.rng_for(33), 8)[0])
     print(json.dumps({"sweep": rows, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
                       "note": "kernel time alone from HIP events around every launch; decode with per-XCD shares"}))
     return 0

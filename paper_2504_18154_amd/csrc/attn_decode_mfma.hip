@@ -172,8 +172,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
     int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, const float* __restrict__ share_in,
-    float* __restrict__ share_out, const float* __restrict__ xcd_speed, int32_t* __restrict__ ws_wave, int B, int Hq,
-    int Hkv, int G, float scale_log2e) {
+    float* __restrict__ share_out, const float* __restrict__ xcd_speed, int32_t* __restrict__ ws_wave,
+    int32_t* __restrict__ ws_cut, int B, int Hq, int Hkv, int G, float scale_log2e) {
   __shared__ int pre[kMaxBatch + 1];
   __shared__ int lens[kMaxBatch];
   __shared__ int wsum[kWaves];
@@ -235,6 +235,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
   const size_t blk_stride = (size_t)Hkv * 4096;
   if (u_begin >= u_end) {
     if (ws_wave && lane == 0) ws_wave[2 * gw] = 0;  // no units: not a sample of this XCD's speed
+    if (ws_cut && lane == 0) ws_cut[4 * gw] = 0;
     return;
   }
 
@@ -368,6 +369,15 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     for (int kk = 0; kk < 4; ++kk) qf[kk] = qn[kk];
     ids = ids_n;
   }
+  if (ws_cut && lane == 0) {
+    // For the merge kernel: a (sequence, K/V head) that starts in this chunk and runs on into later ones
+    // is this chunk's last piece; its partial states are those of this wavefront and the following
+    // n_split - 1.  Every cut (sequence, head) is reported exactly once, by the chunk it starts in.
+    const bool cut = cur.seg_u0 >= u_begin && cur.seg_u0 + cur.nb > u_end;
+    ws_cut[4 * gw] = cut ? ch.owner(cur.seg_u0 + cur.nb - 1) - gw + 1 : 0;
+    ws_cut[4 * gw + 1] = cur.b;
+    ws_cut[4 * gw + 2] = cur.g;
+  }
   if (ws_wave && lane == 0) {  // units streamed and time taken (100 MHz ticks), for the XCD shares
     ws_wave[2 * gw] = (int)(u_end - u_begin);
     ws_wave[2 * gw + 1] = (int)(wall_clock64() - t_start);
@@ -396,6 +406,28 @@ __device__ __forceinline__ void measure_xcd_speed(float* __restrict__ xcd_speed,
   if (threadIdx.x == 0) xcd_speed[x] = n > idle ? v / n : 0.f;
 }
 
+// The n_split partial states of one (sequence, query head), slots base .. base + n_split - 1, into its
+// output row (and log-sum-exp); one wavefront, lanes own pairs of head-vector elements.
+__device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
+                                               size_t base, int n_split, uint16_t* __restrict__ orow,
+                                               float* __restrict__ lse_out) {
+  const int lane = threadIdx.x;
+  float M = -INFINITY;
+  for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[(base + k) * 2]);
+  float lsum = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int k = 0; k < n_split; ++k) {
+    const float w = exp2f(ws_ml[(base + k) * 2] - M);
+    lsum += ws_ml[(base + k) * 2 + 1] * w;
+    const float2 a = *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane);
+    o0 += a.x * w;
+    o1 += a.y * w;
+  }
+  const float inv = 1.f / lsum;
+  const uint32_t w = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
+  *reinterpret_cast<uint32_t*>(orow + 2 * lane) = w;
+  if (lse_out && lane == 0) *lse_out = (M + log2f(lsum)) * kLn2;
+}
+
 // Merge of the partial softmax states of every (sequence, query head) that was cut:
 //   M = max_k m_k;  l = sum_k l_k 2^(m_k - M);  o = sum_k acc_k 2^(m_k - M) / l.
 // grid (Hq, B), 64 threads; lanes own pairs of head-vector elements.
@@ -413,28 +445,34 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
   const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nb;
   const int n_split = ch.owner(seg_u0 + nb - 1) - ch.owner(seg_u0) + 1;
   if (n_split <= 1) return;  // written in final form by the decode kernel
-  const size_t base = ((size_t)b * Hq + h) * ws_splits;
-  const int lane = threadIdx.x;
-  float M = -INFINITY;
-  for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[(base + k) * 2]);
-  float lsum = 0.f, o0 = 0.f, o1 = 0.f;
-  for (int k = 0; k < n_split; ++k) {
-    const float w = exp2f(ws_ml[(base + k) * 2] - M);
-    lsum += ws_ml[(base + k) * 2 + 1] * w;
-    const float2 a = *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane);
-    o0 += a.x * w;
-    o1 += a.y * w;
-  }
-  const float inv = 1.f / lsum;
-  const uint32_t w = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
-  *reinterpret_cast<uint32_t*>(out + ((size_t)b * Hq + h) * 128 + 2 * lane) = w;
-  if (lse && lane == 0) lse[(size_t)b * Hq + h] = (M + log2f(lsum)) * kLn2;
+  merge_partials(ws_acc, ws_ml, ((size_t)b * Hq + h) * ws_splits, n_split, out + ((size_t)b * Hq + h) * 128,
+                 lse ? lse + (size_t)b * Hq + h : nullptr);
+}
+
+// The same merge for the persistent grid, where the decode kernel has listed the cut (sequence, K/V head)s:
+// grid (wavefronts of the decode launch, G), 64 threads; block (w, i) merges query head i of the group that
+// chunk w reported, if it reported one.  A batch of many short sequences has far more (sequence, head)s than
+// cuts, and this grid does not grow with it.
+__global__ __launch_bounds__(64) void decode_cut_merge_kernel(const float* __restrict__ ws_acc,
+                                                             const float* __restrict__ ws_ml,
+                                                             const int32_t* __restrict__ ws_cut, int ws_splits,
+                                                             uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                             float* __restrict__ xcd_speed,
+                                                             const int32_t* __restrict__ ws_wave, int n_waves,
+                                                             int Hq, int G) {
+  const int w = blockIdx.x;
+  if (xcd_speed && w * G + (int)blockIdx.y < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, w * G + blockIdx.y);
+  const int n_split = ws_cut[4 * w];
+  if (n_split <= 1) return;
+  const int b = ws_cut[4 * w + 1], h = ws_cut[4 * w + 2] * G + blockIdx.y;
+  merge_partials(ws_acc, ws_ml, ((size_t)b * Hq + h) * ws_splits, n_split, out + ((size_t)b * Hq + h) * 128,
+                 lse ? lse + (size_t)b * Hq + h : nullptr);
 }
 
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta,
                               int32_t ws_splits, const float* share_in, float* share_out, const float* xcd_speed,
-                              int32_t* ws_wave, hipStream_t s) {
+                              int32_t* ws_wave, int32_t* ws_cut, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   int n_wg = n_persistent_wgs;
   int c_forced = 0;
@@ -445,19 +483,26 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
     const long long waves = (u_max + c_forced - 1) / c_forced;
     n_wg = (int)((waves + kWaves - 1) / kWaves);
     share_in = nullptr;
+    ws_cut = nullptr;  // sized for the persistent grid only
   }
   if (n_wg % 8 != 0) share_in = nullptr;  // the rounds of 8 workgroups would not line up with the XCDs
   if (!share_in) ws_wave = nullptr;
   hipLaunchKernelGGL(decode_mfma_kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q,
                      a.q_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
-                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out, xcd_speed, ws_wave, a.B, a.Hq,
-                     a.Hkv, G, a.scale_log2e);
+                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out, xcd_speed, ws_wave, ws_cut,
+                     a.B, a.Hq, a.Hkv, G, a.scale_log2e);
   return hipGetLastError();
 }
 
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
                                     const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
-                                    const int32_t* ws_wave, int32_t n_waves, hipStream_t s) {
+                                    const int32_t* ws_wave, const int32_t* ws_cut, int32_t n_waves, hipStream_t s) {
+  if (ws_cut) {
+    hipLaunchKernelGGL(decode_cut_merge_kernel, dim3((unsigned)n_waves, (unsigned)(a.Hq / a.Hkv)), dim3(64), 0, s,
+                       ws_acc, ws_ml, ws_cut, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq,
+                       a.Hq / a.Hkv);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(decode_flat_merge_kernel, dim3((unsigned)a.Hq, (unsigned)a.B), dim3(64), 0, s, ws_acc, ws_ml,
                      ws_meta, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq, a.Hkv,
                      a.Hq / a.Hkv);

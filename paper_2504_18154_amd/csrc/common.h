@@ -84,7 +84,8 @@ struct ecoserve_ctx {
   float* ws_acc;               // [max_batch][Hq][ws_splits][D]
   float* ws_ml;                // [max_batch][Hq][ws_splits][2]
   int32_t* ws_meta;            // [max_batch + 19]: chunk sizes and batch prefix sums of the last decode launch
-  float* ws_share;             // per-XCD shares (mean 1) [2][8], speeds [8], then as int32 [2 * wavefronts]: units, ticks
+  float* ws_share;             // per-XCD shares (mean 1) [2][8], speeds [8], then as int32 [2 * wavefronts]: units, ticks,
+                               // then [4 * wavefronts]: the cut (sequence, K/V head) each chunk reports to the merge
   int share_parity;            // which of the two share vectors the next adaptive decode launch reads
   int32_t ws_splits;
   int32_t* ws_plan;            // prefill plan: header and one record per query tile of the last prefill launch
@@ -143,10 +144,10 @@ hipError_t launch_decode_merge(const AttnArgs& a, const int32_t* ctx_len, int32_
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
                               const float* share_in, float* share_out, const float* xcd_speed, int32_t* ws_wave,
-                              hipStream_t s);
+                              int32_t* ws_cut, hipStream_t s);
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
                                     const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
-                                    const int32_t* ws_wave, int32_t n_waves, hipStream_t s);
+                                    const int32_t* ws_wave, const int32_t* ws_cut, int32_t n_waves, hipStream_t s);
 
 // attn_prefill_mfma.hip: bf16, D = 128
 // (ws_plan must hold kPlanHeaderInts + prefill_plan_tiles(B, T) * kRecInts int32; make_plan false: the tile list

@@ -77,6 +77,36 @@ def lengths_lognormal(rng, n: int, mean: float, sigma: float, lo: int, hi: int) 
     return np.clip(np.rint(x), lo, hi).astype(np.int32)
 
 
+# Table 4 of the paper: (input average, input median, output average, output median) of the three datasets.
+TABLE4 = {"alpaca": (20.63, 17.0, 163.80, 119.0), "sharegpt": (343.76, 148.0, 237.20, 152.0),
+          "longbench": (2686.89, 2736.5, 101.78, 19.0)}
+
+
+def table4_lengths(name: str, rng, n: int, max_len: int = 4096):
+    """(input, output) token counts shaped like one dataset of Table 4: lognormal with the table's average
+    and median where the average exceeds the median (sigma^2 = 2 ln(avg / median)), else (LongBench inputs)
+    normal around the average with a third of it as deviation; inputs are cut at `max_len` as in Section 5.1."""
+    in_avg, in_med, out_avg, out_med = TABLE4[name]
+
+    def draw(avg, med, lo, hi):
+        if avg > med:
+            sigma = math.sqrt(2.0 * math.log(avg / med))
+            return lengths_lognormal(rng, n, avg, sigma, lo, hi)
+        return np.clip(np.rint(rng.normal(avg, avg / 3.0, size=n)), lo, hi).astype(np.int32)
+
+    return draw(in_avg, in_med, 1, max_len), draw(out_avg, out_med, 1, max_len)
+
+
+def table4_decode_batch(model: ModelShape, name: str, B: int, seed: int) -> "DecodeBatch":
+    """A decode-only batch in steady state on one dataset's shape: every sequence holds its prompt and a
+    uniformly drawn part of its output."""
+    rng = rng_for(seed)
+    n_in, n_out = table4_lengths(name, rng, B)
+    ctx = (n_in + np.floor(rng.random(B) * n_out).astype(np.int32) + 1).astype(np.int32)
+    table, nb = make_block_table(rng, ctx.astype(np.int64), model.bs)
+    return DecodeBatch(model, ctx, table, nb, seed)
+
+
 def make_block_table(rng, capacity_tokens, bs: int = BLOCK_SIZE, pool_factor: float = 1.1,
                      min_spare: int = 2, stride: int | None = None):
     """Block table for sequences that may grow to capacity_tokens[b] tokens.

@@ -72,3 +72,20 @@ def test_workload_recipes_are_seeded_and_in_range():
     assert table.shape[1] >= (8192 + 64 + 15) // 16
     t = wl.config1_tiny()
     assert list(t.q_len) == [37, 100] and t.block_table.shape == (2, 7)
+
+
+def test_table4_shaped_lengths_reproduce_the_table():
+    """The synthetic stand-ins for the paper's datasets have Table 4's averages and medians
+    (inputs are cut at 4096 tokens as in Section 5.1, which lowers ShareGPT's input average a little)."""
+    for name, (in_avg, in_med, out_avg, out_med) in wl.TABLE4.items():
+        n_in, n_out = wl.table4_lengths(name, wl.rng_for(5), 40000)
+        assert n_in.min() >= 1 and n_in.max() <= 4096 and n_out.min() >= 1
+        assert abs(np.median(n_in) - in_med) <= 0.03 * in_med + 1
+        assert abs(np.median(n_out) - out_med) <= 0.03 * out_med + 1
+        assert abs(n_out.mean() - out_avg) <= 0.10 * out_avg   # the cut at 4096 trims LongBench's heavy tail
+        assert in_avg * (0.93 if name == "sharegpt" else 0.97) <= n_in.mean() <= 1.03 * in_avg
+    db = wl.table4_decode_batch(wl.M30B, "sharegpt", 64, 9)
+    assert db.B == 64 and db.ctx_len.min() >= 2
+    used = db.block_table[db.block_table >= 0]
+    assert len(np.unique(used)) == len(used) and used.max() < db.num_blocks
+    assert all((db.block_table[i, :(n + 15) // 16] >= 0).all() for i, n in enumerate(db.ctx_len))
