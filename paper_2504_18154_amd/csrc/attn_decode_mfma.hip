@@ -42,10 +42,13 @@
 namespace eco {
 
 constexpr int kWaves = 4;
-#ifndef ECO_DECODE_DEPTH
-#define ECO_DECODE_DEPTH 4
-#endif
-constexpr int kDepth = ECO_DECODE_DEPTH;  // cache blocks in flight per wavefront (8 KiB each)
+// The kernel comes in two shapes (template arguments: cache blocks of 8 KiB in flight per wavefront,
+// workgroups per CU).  <4, 1> is the streaming shape: one wavefront per SIMD with the whole register
+// budget; a second wavefront per SIMD buys nothing there (the memory pipeline serves the older one
+// first).  <3, 2> is for batches cut into many short pieces (hundreds of short sequences): a piece ends
+// with the pipeline drained and a few stores, and only another wavefront on the SIMD can fill that gap
+// (measured: 1024 sequences of ~100 tokens 171 -> 145 us, 512 of ~400 tokens 208 -> 195 us; the
+// benchmark's 128 sequences of 512..4096 tokens 228 -> 229 us).
 
 struct KVFrag {
   bf16x8 k[4];   // K block: unit (4*kk + quad, token = col)  ->  A operand of S^T step kk
@@ -167,7 +170,8 @@ struct Chunking {
 };
 constexpr int kMetaPre = 18;  // ws_meta: [0..7] c, [8..16] cum, then the batch prefix sums
 
-__global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
+template <int kDepth, int kWgsPerCu>
+__global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
     const uint16_t* __restrict__ q, int q_row_stride, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
@@ -472,7 +476,7 @@ __global__ __launch_bounds__(64) void decode_cut_merge_kernel(const float* __res
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta,
                               int32_t ws_splits, const float* share_in, float* share_out, const float* xcd_speed,
-                              int32_t* ws_wave, int32_t* ws_cut, hipStream_t s) {
+                              int32_t* ws_wave, int32_t* ws_cut, bool two_per_cu, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   int n_wg = n_persistent_wgs;
   int c_forced = 0;
@@ -487,10 +491,16 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   }
   if (n_wg % 8 != 0) share_in = nullptr;  // the rounds of 8 workgroups would not line up with the XCDs
   if (!share_in) ws_wave = nullptr;
-  hipLaunchKernelGGL(decode_mfma_kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q,
-                     a.q_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
-                     (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out, xcd_speed, ws_wave, ws_cut,
-                     a.B, a.Hq, a.Hkv, G, a.scale_log2e);
+  auto launch = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q, a.q_row_stride,
+                       (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
+                       (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out,
+                       xcd_speed, ws_wave, ws_cut, a.B, a.Hq, a.Hkv, G, a.scale_log2e);
+  };
+  if (two_per_cu)
+    launch(decode_mfma_kernel<3, 2>);
+  else
+    launch(decode_mfma_kernel<4, 1>);
   return hipGetLastError();
 }
 

@@ -257,6 +257,34 @@ def test_append_at_the_largest_batch(dtype):
     layer.close()
 
 
+def test_bf16_decode_of_hundreds_of_short_sequences():
+    """420 sequences of 1..300 tokens with 8 K/V heads: more than three (sequence, head) pieces per
+    wavefront of the one-workgroup-per-CU grid, so the library launches its two-workgroups-per-CU shape,
+    and nearly every (sequence, head) is written in final form by the decode kernel while the merge
+    handles the few that a chunk boundary cuts.  Equal and measured per-XCD shares."""
+    from paper_2504_18154_amd import binding
+    model = M30
+    rng = np.random.default_rng(47)
+    lens = rng.integers(1, 301, size=420)
+    lens[[0, 1, 419]] = [1, 300, 16]
+    say(f"bf16 decode of {len(lens)} short sequences, {int(lens.sum())} tokens")
+    pb, layer = _mk(model, lens, seed=48)
+    _, k, v = _qkv(model, pb.T, 470)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    layer.assert_cache_bit_exact()
+    q = wl.randn((pb.B, model.Hq, model.D), "bf16", 471)
+    ref, ref_lse = layer.decode_oracle(q, pb.block_table, pb.q_len)
+    out, lse = layer.decode_gpu(q, pb.block_table, pb.q_len)
+    compare("decode, equal shares", out, ref, "bf16")
+    compare_lse("decode, equal shares", lse, ref_lse, "bf16")
+    layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
+    for call in range(4):
+        out, lse = layer.decode_gpu(q, pb.block_table, pb.q_len)
+        compare(f"decode, measured shares, call {call}", out, ref, "bf16")
+        compare_lse(f"decode, measured shares, call {call}", lse, ref_lse, "bf16")
+    layer.close()
+
+
 def test_bf16_short_chunk_after_long_prefix():
     """A few new tokens behind thousands of cached ones (one query tile, many key steps) next to a
     long new prompt: the work items differ by two orders of magnitude."""
