@@ -169,6 +169,9 @@ def main() -> int:
     ap.add_argument("--fused-qkv", action="store_true",
                     help="Q, K and V are slices of one row [Hq + 2 Hkv][D] per token (the output of a fused projection, "
                          "Eq. 1) and are read in place through the strided calls; default: three packed arrays")
+    ap.add_argument("--fused-append", action="store_true",
+                    help="decode phase: one call per layer that appends the new tokens inside the decode launch "
+                         "(default: kv_append and attn_decode as two calls)")
     ap.add_argument("--event-every", type=int, default=7,
                     help="bracket every n-th launch of each kernel with HIP events inside the timed region (an event pair "
                          "per launch delays the stream by several microseconds per layer; 1 = every launch)")
@@ -317,8 +320,11 @@ def main() -> int:
             for l in range(layers):
                 kc, vc = d_pools[l]
                 kn, vn = (d_knew0, d_vnew0) if l == 0 else (d_knew, d_vnew)
-                append(dctx)(kc, vc, kn, vn, d_cu, d_before, d_bt, max_new_len=1)
-                decode(d_q, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
+                if args.fused_append:
+                    dctx.attn_decode_append(d_q, kn, vn, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
+                else:
+                    append(dctx)(kc, vc, kn, vn, d_cu, d_before, d_bt, max_new_len=1)
+                    decode(d_q, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
         t[2].record()
         if timers is not None:
             timers.append(t)
@@ -369,6 +375,7 @@ def main() -> int:
                         "block 16; append + attention per layer",
             "layers": layers, "phase": args.phase, "decode_shares": "equal" if args.equal_shares else "per-XCD, measured",
             "prefill_tile_list": "built once per step, shared by the layers",
+            "decode_append": "fused into the decode launch" if args.fused_append else "a launch of its own",
             "qkv_rows": "slices of fused rows [tokens, Hq + 2 Hkv, D], read in place" if args.fused_qkv
                         else "three packed arrays",
             "kernel_events": "every launch" if args.prefill_chunk or args.event_every <= 1
@@ -387,12 +394,12 @@ def main() -> int:
             return None
 
     if do_dec:
-        # phase time includes the one-token appends and the merge kernels: whole decode phase
+        # phase time includes the one-token appends (fused or not) and the merge kernels: whole decode phase
         res["value"] = rate(dec_bytes_layer * layers, dec_ms) / 1e9
         res["decode"] = {
             "ms_per_layer": dec_ms / layers, "phase_ms": dec_ms, "GBps": res["value"],
             "frac_of_hbm_peak": res["value"] / acc.PEAK_HBM_GBPS,
-            "append_us_per_layer": 1e3 * k_dapp_ms / max(k_dapp_n, 1),
+            "append_us_per_layer": 1e3 * k_dapp_ms / k_dapp_n if k_dapp_n else None,
         }
         avg_ms = k_dec_ms / max(k_dec_n, 1)
         a = rate(dec_bytes_layer, avg_ms) / 1e9

@@ -257,6 +257,27 @@ int ecoserve_attn_decode_strided(ecoserve_ctx* ctx, const void* q, int64_t q_row
                                  void* stream);
 
 /*
+ * Decode attention with the step's cache append fused in (Section 2.1: in the
+ * decode phase every sequence brings exactly one new token, whose key and
+ * value join the cache and whose query attends to the whole context).
+ * Equivalent, bit for bit in cache and output, to ecoserve_kv_append_strided
+ * of one token per sequence at position ctx_len[b] - 1 followed by
+ * ecoserve_attn_decode_strided, in one launch less: the wavefront that
+ * streams a sequence's last cache block takes the new token's K and V from
+ * the new rows and stores them into the block.
+ *
+ *   k_new, v_new     : dev, row b = the new token of sequence b, [Hkv][D], rows
+ *                      new_row_stride elements apart (rules of the strided calls)
+ *   k_cache, v_cache : dev, in/out
+ *   ctx_len          : dev, int32[B], context lengths INCLUDING the new token (>= 1)
+ *   everything else as in ecoserve_attn_decode_strided.
+ */
+int ecoserve_attn_decode_append(ecoserve_ctx* ctx, const void* q, int64_t q_row_stride, const void* k_new,
+                                const void* v_new, int64_t new_row_stride, void* k_cache, void* v_cache,
+                                const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len,
+                                void* out, float* lse, int32_t B, int32_t max_ctx_len, void* stream);
+
+/*
  * Machine ceilings for the roofline reasoning of Section 2.2 (Table 2 prices
  * decode attention in bytes read, prefill attention in matrix FLOPs): what
  * `device` sustains on each resource, to be reported beside the published

@@ -27,6 +27,7 @@ EXPORTS = [
     "ecoserve_attn_prefill", "ecoserve_attn_decode", "ecoserve_debug_validate", "ecoserve_profile_read",
     "ecoserve_profile_reset", "ecoserve_probe_hbm_read", "ecoserve_probe_mfma_bf16",
     "ecoserve_kv_append_strided", "ecoserve_attn_prefill_strided", "ecoserve_attn_decode_strided",
+    "ecoserve_attn_decode_append",
 ]
 
 
@@ -67,6 +68,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.ecoserve_kv_append_strided.argtypes = [vp, vp, vp, vp, vp, i64, i32p, i32p, i32p, i32, i32, i32, i32, vp]
     lib.ecoserve_attn_prefill_strided.argtypes = [vp, vp, i64, vp, vp, i32p, i32p, i32p, i32, vp, vp, i32, i32, i32, vp]
     lib.ecoserve_attn_decode_strided.argtypes = [vp, vp, i64, vp, vp, i32p, i32, i32p, vp, vp, i32, i32, vp]
+    lib.ecoserve_attn_decode_append.argtypes = [vp, vp, i64, vp, vp, i64, vp, vp, i32p, i32, i32p, vp, vp, i32, i32, vp]
     lib.ecoserve_debug_validate.argtypes = [vp, i32p, i32p, i32p, i32, i32]
     lib.ecoserve_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ecoserve_profile_reset.argtypes = [vp]
@@ -238,6 +240,16 @@ class Context:
                                                  _ptr(block_table), int(block_table.shape[1]), _ptr(ctx_len),
                                                  _ptr(out), _ptr(lse), int(B), int(max_ctx_len), _stream()),
                "ecoserve_attn_decode_strided")
+
+    def attn_decode_append(self, q, k_new, v_new, k_cache, v_cache, block_table, ctx_len, out, max_ctx_len, lse=None):
+        """Decode with the append of the step's one new token per sequence fused in (ctx_len counts it)."""
+        B = ctx_len.numel()
+        if _row_stride(k_new) != _row_stride(v_new):
+            raise ValueError("k_new and v_new must have the same row stride")
+        _check(_lib.ecoserve_attn_decode_append(self._h, _ptr(q), _row_stride(q), _ptr(k_new), _ptr(v_new),
+                                                _row_stride(k_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                                int(block_table.shape[1]), _ptr(ctx_len), _ptr(out), _ptr(lse), int(B),
+                                                int(max_ctx_len), _stream()), "ecoserve_attn_decode_append")
 
     def attn_decode(self, q, k_cache, v_cache, block_table, ctx_len, out, max_ctx_len, lse=None):
         B = ctx_len.numel()

@@ -280,7 +280,7 @@ int ecoserve_kv_append_strided(ecoserve_ctx* c, void* k_cache, void* v_cache, co
   hipStream_t s = (hipStream_t)stream;
   ProfileScope prof(c, ECOSERVE_KERNEL_APPEND, s);
   const hipError_t e = launch_kv_append(c, k_cache, v_cache, k_new, v_new, (int32_t)new_row_stride, cu_q, ctx_before,
-                                        block_table, bt_stride, B, T, max_new_len, s);
+                                        block_table, bt_stride, B, T, max_new_len, 0, s);
   return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
 }
 
@@ -289,6 +289,9 @@ static AttnArgs make_args(const ecoserve_ctx* c, const void* q, int64_t q_row_st
   AttnArgs a;
   a.q = q;
   a.q_row_stride = (int32_t)q_row_stride;
+  a.k_new = nullptr;
+  a.v_new = nullptr;
+  a.new_row_stride = 0;
   a.k_cache = k_cache;
   a.v_cache = v_cache;
   a.block_table = block_table;
@@ -356,6 +359,11 @@ int ecoserve_attn_prefill_strided(ecoserve_ctx* c, const void* q, int64_t q_row_
   return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
 }
 
+static int decode_impl(ecoserve_ctx* c, const void* q, int64_t q_row_stride, const void* k_new, const void* v_new,
+                       int64_t new_row_stride, void* k_cache, void* v_cache,
+                       const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len, void* out, float* lse,
+                       int32_t B, int32_t max_ctx_len, void* stream);
+
 int ecoserve_attn_decode(ecoserve_ctx* c, const void* q, const void* k_cache, const void* v_cache,
                          const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len, void* out,
                          float* lse, int32_t B, int32_t max_ctx_len, void* stream) {
@@ -368,6 +376,25 @@ int ecoserve_attn_decode_strided(ecoserve_ctx* c, const void* q, int64_t q_row_s
                                  const void* v_cache, const int32_t* block_table, int32_t bt_stride,
                                  const int32_t* ctx_len, void* out, float* lse, int32_t B, int32_t max_ctx_len,
                                  void* stream) {
+  return decode_impl(c, q, q_row_stride, nullptr, nullptr, 0, const_cast<void*>(k_cache),
+                     const_cast<void*>(v_cache), block_table, bt_stride, ctx_len, out, lse, B, max_ctx_len, stream);
+}
+
+int ecoserve_attn_decode_append(ecoserve_ctx* c, const void* q, int64_t q_row_stride, const void* k_new,
+                                const void* v_new, int64_t new_row_stride, void* k_cache,
+                                void* v_cache, const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len,
+                                void* out, float* lse, int32_t B, int32_t max_ctx_len, void* stream) {
+  if (!c || !stride_ok(c, new_row_stride, c->lay.num_kv_heads)) return ECOSERVE_EINVAL;
+  if (B > 0 && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new))) return ECOSERVE_EINVAL;
+  return decode_impl(c, q, q_row_stride, k_new, v_new, new_row_stride, k_cache, v_cache, block_table,
+                     bt_stride, ctx_len, out, lse, B, max_ctx_len, stream);
+}
+
+// Decode, with the step's append fused in if k_new is given.
+static int decode_impl(ecoserve_ctx* c, const void* q, int64_t q_row_stride, const void* k_new, const void* v_new,
+                       int64_t new_row_stride, void* k_cache, void* v_cache,
+                       const int32_t* block_table, int32_t bt_stride, const int32_t* ctx_len, void* out, float* lse,
+                       int32_t B, int32_t max_ctx_len, void* stream) {
   if (!c || B < 0 || max_ctx_len < 0) return ECOSERVE_EINVAL;
   if (!stride_ok(c, q_row_stride, c->lay.num_q_heads)) return ECOSERVE_EINVAL;
   if (B == 0) return ECOSERVE_OK;
@@ -381,9 +408,19 @@ int ecoserve_attn_decode_strided(ecoserve_ctx* c, const void* q, int64_t q_row_s
   DeviceGuard guard(c->device);
   if (!guard.ok) return ECOSERVE_EHIP;
   hipStream_t s = (hipStream_t)stream;
-  const AttnArgs a = make_args(c, q, q_row_stride, k_cache, v_cache, block_table, bt_stride, out, lse, B);
+  AttnArgs a = make_args(c, q, q_row_stride, k_cache, v_cache, block_table, bt_stride, out, lse, B);
   hipError_t e;
+  if (k_new && !use_mfma(c)) {
+    // the plain kernels do not fuse: the one-token append runs as its own kernel first (position = ctx_len - 1)
+    ProfileScope prof(c, ECOSERVE_KERNEL_APPEND, s);
+    e = launch_kv_append(c, k_cache, v_cache, k_new, v_new, (int32_t)new_row_stride, nullptr, ctx_len, block_table,
+                         bt_stride, B, B, 1, -1, s);
+    if (e != hipSuccess) return ECOSERVE_EHIP;
+  }
   if (use_mfma(c)) {
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.new_row_stride = (int32_t)new_row_stride;
     // many short pieces per wavefront (hundreds of short sequences): two workgroups per CU fill each other's gaps
     const bool two_per_cu = c->opt_split_tokens == 0 &&
                             (int64_t)B * c->lay.num_kv_heads >= (int64_t)kDecodeManyPieces * c->num_cu * kDecodeWgsPerCu * 4;

@@ -172,7 +172,9 @@ constexpr int kMetaPre = 18;  // ws_meta: [0..7] c, [8..16] cum, then the batch 
 
 template <int kDepth, int kWgsPerCu>
 __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
-    const uint16_t* __restrict__ q, int q_row_stride, const char* __restrict__ k_cache, const char* __restrict__ v_cache,
+    const uint16_t* __restrict__ q, int q_row_stride, const uint16_t* __restrict__ k_new,
+    const uint16_t* __restrict__ v_new, int new_row_stride, const char* __restrict__ k_cache,
+    const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
     int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, const float* __restrict__ share_in,
@@ -182,6 +184,7 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
   __shared__ int lens[kMaxBatch];
   __shared__ int wsum[kWaves];
   __shared__ int s_c[8], s_cum[9];
+  __shared__ __attribute__((aligned(16))) uint16_t s_new[kWaves][256];  // fused append: a token's K row, then its V row
   const long long t_start = wall_clock64();
   scan_block_counts(pre, lens, wsum, ctx_len, B);
 
@@ -304,6 +307,13 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
     }
     const size_t head_off = (size_t)cur.g * 4096;
     const int L = cur.L;
+    // fused append: if this piece reaches the end of its sequence, the new token's K and V rows (512 bytes)
+    // are fetched now, 8 bytes per lane, and wait in two registers until the last block is worked on
+    u32x2 new_row = {0u, 0u};
+    if (k_new != nullptr && cur.blk0 + cur.n == cur.nb) {
+      const size_t row = (size_t)cur.b * new_row_stride + (size_t)cur.g * 128 + (lane & 31) * 4;
+      new_row = *reinterpret_cast<const u32x2*>((lane < 32 ? k_new : v_new) + row);
+    }
 
     f32x4 acc[8];
 #pragma unroll
@@ -322,7 +332,40 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
         const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, ii) * blk_stride + head_off;
         load_block(f, k_cache + off, v_cache + off, lane, col, quad);
       };
-      auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // >= 16 except in the sequence's last block
+      auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // > 16 except in the sequence's last block
+      // Fused append (k_new given): the sequence's newest token, slot t of its last block, is not in the
+      // cache yet.  The wavefront that streams that block (exactly one per K/V head) takes the token's K
+      // and V from the new rows instead, in the operand layout the block's loads produce, and writes them
+      // to the slot, which nothing else in this launch reads.
+      auto append_token = [&](KVFrag& fr, int i, int t) {
+        const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, i) * blk_stride + head_off;
+        char* const kb = const_cast<char*>(k_cache) + off;
+        char* const vb = const_cast<char*>(v_cache) + off;
+        // through LDS into the operand layout: lane l holds bytes [8 l, 8 l + 8) of (K row, V row)
+        uint16_t* const st = s_new[wave];
+        *reinterpret_cast<u32x2*>(st + lane * 4) = new_row;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (col == t) {
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 x = *reinterpret_cast<const bf16x8*>(st + kk * 32 + quad * 8);
+            fr.k[kk] = x;
+            *reinterpret_cast<bf16x8*>(kb + kk * 1024 + lane * 16) = x;
+          }
+        }
+        if (quad == (t >> 2)) {
+#pragma unroll
+          for (int dt = 0; dt < 8; ++dt) {
+            const short x = (short)st[128 + dt * 16 + col];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (e == (t & 3)) fr.v[dt][e] = x;
+            *reinterpret_cast<short*>(vb + dt * 512 + col * 32 + quad * 8 + (t & 3) * 2) = x;
+          }
+        }
+      };
       KVFrag f[kDepth];
 #pragma unroll
       for (int d = 0; d < kDepth - 1; ++d) issue(f[d], d);
@@ -332,7 +375,12 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
         for (int d = 0; d < kDepth; ++d) {
           if (!done) {
             issue(f[(d + kDepth - 1) % kDepth], i + d + kDepth - 1);
-            process_block(f[d], qf, acc, m, l, tail_of(i + d), quad, scale_log2e);
+            const int tail = tail_of(i + d);
+            if (k_new != nullptr && tail <= 16) {
+              asm volatile("" ::: "memory");  // (a real branch: once per (sequence, head))
+              append_token(f[d], i + d, tail - 1);
+            }
+            process_block(f[d], qf, acc, m, l, tail, quad, scale_log2e);
             done = i + d + 1 >= n;
           }
         }
@@ -493,7 +541,7 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   if (!share_in) ws_wave = nullptr;
   auto launch = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q, a.q_row_stride,
-                       (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
+                       (const uint16_t*)a.k_new, (const uint16_t*)a.v_new, a.new_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
                        (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out,
                        xcd_speed, ws_wave, ws_cut, a.B, a.Hq, a.Hkv, G, a.scale_log2e);
   };

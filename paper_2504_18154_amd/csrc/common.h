@@ -111,6 +111,9 @@ namespace eco {
 struct AttnArgs {
   const void* q;
   int32_t q_row_stride;  // elements between the query rows of consecutive tokens (>= Hq * D)
+  const void* k_new;     // decode with the append fused in: the step's new K and V rows, else NULL
+  const void* v_new;
+  int32_t new_row_stride;
   const void* k_cache;
   const void* v_cache;
   const int32_t* block_table;
@@ -124,11 +127,13 @@ struct AttnArgs {
 };
 
 // kv_append.hip
-// (new_row_stride: elements between the K rows, and between the V rows, of consecutive tokens)
+// (new_row_stride: elements between the K rows, and between the V rows, of consecutive tokens.  With
+// max_new_len <= 1, cu_q may be NULL: one token per sequence, token b for sequence b, stored at position
+// ctx_before[b] + pos_bias; otherwise pos_bias must be 0.)
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
                             const void* v_new, int32_t new_row_stride, const int32_t* cu_q, const int32_t* ctx_before,
                             const int32_t* block_table, int32_t bt_stride, int32_t B, int32_t T,
-                            int32_t max_new_len, hipStream_t s);
+                            int32_t max_new_len, int32_t pos_bias, hipStream_t s);
 
 // attn_plain.hip: any head size / dtype, no matrix cores
 hipError_t launch_prefill_plain(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,

@@ -167,15 +167,17 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_one_kernel(E* __rest
                                                                         const int32_t* __restrict__ cu_q,
                                                                         const int32_t* __restrict__ ctx_before,
                                                                         const int32_t* __restrict__ block_table,
-                                                                        int bt_stride, int B, int Hkv, int D) {
+                                                                        int bt_stride, int B, int Hkv, int D,
+                                                                        int pos_bias) {
   constexpr int X = Elem<E>::X;
   typedef uint32_t u4 __attribute__((ext_vector_type(4)));
   const int pair = blockIdx.x * (kAppendThreads / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (pair >= B * Hkv) return;
   const int b = pair / Hkv, g = pair % Hkv;
-  const int tok = cu_q[b];
-  if (cu_q[b + 1] - tok <= 0) return;
-  const int p = ctx_before[b], slot = p & 15;
+  // cu_q == NULL: exactly one token per sequence, token b belongs to sequence b
+  const int tok = cu_q ? cu_q[b] : b;
+  if (cu_q && cu_q[b + 1] - tok <= 0) return;
+  const int p = ctx_before[b] + pos_bias, slot = p & 15;
   const int64_t blk = block_table[(size_t)b * bt_stride + (p >> 4)];
   const E* ksrc = k_new + (size_t)tok * new_row_stride + g * D;
   E* kdst = k_cache + ((size_t)blk * Hkv + g) * 16 * D + (size_t)slot * X;
@@ -213,13 +215,14 @@ static void launch_tiled(const ecoserve_layout& L, void* k_cache, void* v_cache,
 template <typename E>
 static void launch_typed(const ecoserve_layout& L, void* k_cache, void* v_cache, const void* k_new, const void* v_new,
                          int32_t new_row_stride, const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
-                         int32_t bt_stride, int32_t B, int32_t T, int32_t max_new_len, hipStream_t s) {
+                         int32_t bt_stride, int32_t B, int32_t T, int32_t max_new_len, int32_t pos_bias,
+                         hipStream_t s) {
   if (max_new_len <= 1) {
     const int per_wg = kAppendThreads / 64;
     const dim3 grid((unsigned)(((int64_t)B * L.num_kv_heads + per_wg - 1) / per_wg));
     hipLaunchKernelGGL((kv_append_one_kernel<E>), grid, dim3(kAppendThreads), 0, s, (E*)k_cache, (E*)v_cache,
                        (const E*)k_new, (const E*)v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B,
-                       L.num_kv_heads, L.head_dim);
+                       L.num_kv_heads, L.head_dim, pos_bias);
   } else if (L.num_kv_heads % 4 == 0) {
     launch_tiled<E, 4>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T, s);
   } else if (L.num_kv_heads % 2 == 0) {
@@ -232,14 +235,14 @@ static void launch_typed(const ecoserve_layout& L, void* k_cache, void* v_cache,
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
                             const void* v_new, int32_t new_row_stride, const int32_t* cu_q,
                             const int32_t* ctx_before, const int32_t* block_table, int32_t bt_stride, int32_t B,
-                            int32_t T, int32_t max_new_len, hipStream_t s) {
+                            int32_t T, int32_t max_new_len, int32_t pos_bias, hipStream_t s) {
   const ecoserve_layout& L = ctx->lay;
   if (L.dtype == ECOSERVE_BF16)
     launch_typed<uint16_t>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T,
-                           max_new_len, s);
+                           max_new_len, pos_bias, s);
   else
     launch_typed<float>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T,
-                        max_new_len, s);
+                        max_new_len, pos_bias, s);
   return hipGetLastError();
 }
 

@@ -285,6 +285,59 @@ def test_bf16_decode_of_hundreds_of_short_sequences():
     layer.close()
 
 
+@pytest.mark.parametrize("shape", ["bf16-G5", "bf16-mha", "bf16-many-short", "f32-plain"])
+def test_decode_with_the_append_fused_in(shape):
+    """ecoserve_attn_decode_append against the two separate calls on a copy of the same cache: cache and
+    output must agree bit for bit, step after step (positions crossing block boundaries, contexts that end
+    on a block boundary, a sequence whose first token is the appended one), and against the oracle."""
+    from paper_2504_18154_amd import binding
+    if shape == "f32-plain":
+        model, lens = wl.ModelShape("small-f32", 4, 2, 64, 1, "f32"), [0, 15, 16, 17, 100]
+    elif shape == "bf16-mha":
+        model, lens = wl.ModelShape("mha", 6, 6, 128, 1, "bf16"), [0, 15, 16, 31, 32, 700]
+    elif shape == "bf16-many-short":
+        model, lens = M30, list(np.random.default_rng(49).integers(0, 200, size=400))
+    else:
+        model, lens = M30, [0, 1, 14, 15, 16, 17, 255, 256, 1000, 2047, 3000]
+    steps = 3
+    say(f"fused append + decode, {shape}: {len(lens)} sequences, {steps} steps")
+    lens = np.asarray(lens, dtype=np.int32)
+    pb, layer = _mk(model, lens + steps, seed=62)
+    table = dev_i32(pb.block_table)
+    if lens.sum() > 0:
+        _, k, v = _qkv(model, int(lens.sum()), 620)
+        layer.append(k, v, wl.cu_from_lengths(lens), np.zeros(len(lens), np.int32), pb.block_table)
+    kc2, vc2 = layer.kc.clone(), layer.vc.clone()     # the fused call works on its own copy
+    B = len(lens)
+    ones = dev_i32(wl.cu_from_lengths([1] * B))
+    ctx = lens.copy()
+    for step in range(steps):
+        rows = wl.randn((B, (model.Hq + 2 * model.Hkv) * model.D), model.dtype, 630 + step, device="cuda")
+        body = rows.unflatten(1, (model.Hq + 2 * model.Hkv, model.D))
+        q, kn, vn = body[:, :model.Hq], body[:, model.Hq:model.Hq + model.Hkv], body[:, model.Hq + model.Hkv:]
+        # separate calls (and the oracle's cache) ...
+        layer.ctx.kv_append_strided(layer.kc, layer.vc, kn, vn, ones, dev_i32(ctx), table, max_new_len=1)
+        orc.kv_append(layer.shape, layer.okc, layer.ovc, wl.to_bits(kn), wl.to_bits(vn), wl.cu_from_lengths([1] * B),
+                      ctx, pb.block_table)
+        ctx = ctx + 1
+        want = torch.full((B, model.Hq, model.D), float("nan"), dtype=q.dtype, device="cuda")
+        want_lse = torch.full((B, model.Hq), float("nan"), dtype=torch.float32, device="cuda")
+        layer.ctx.attn_decode_strided(q, layer.kc, layer.vc, table, dev_i32(ctx), want, int(ctx.max()), want_lse)
+        # ... against the fused call
+        out, lse = torch.full_like(want, float("nan")), torch.full_like(want_lse, float("nan"))
+        layer.ctx.attn_decode_append(q, kn, vn, kc2, vc2, table, dev_i32(ctx), out, int(ctx.max()), lse)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.uint8), want.view(torch.uint8)), f"step {step}: outputs differ"
+        assert torch.equal(lse, want_lse), f"step {step}: log-sum-exp differs"
+        assert torch.equal(kc2.view(torch.uint8), layer.kc.view(torch.uint8)), f"step {step}: K pools differ"
+        assert torch.equal(vc2.view(torch.uint8), layer.vc.view(torch.uint8)), f"step {step}: V pools differ"
+        layer.assert_cache_bit_exact()
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, ctx)
+        compare(f"fused decode step {step}", out, ref, model.dtype)
+        compare_lse(f"fused decode step {step}", lse, ref_lse, model.dtype)
+    layer.close()
+
+
 def test_bf16_short_chunk_after_long_prefix():
     """A few new tokens behind thousands of cached ones (one query tile, many key steps) next to a
     long new prompt: the work items differ by two orders of magnitude."""
