@@ -35,6 +35,15 @@ def test_library_exports_every_declared_symbol(binding):
     assert sorted(binding.EXPORTS) == names
 
 
+def test_library_exports_every_symbol_of_the_scheduling_header(binding):
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "ecoserve_padg.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(ecoserve_padg_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["ecoserve_padg_check_constraints", "ecoserve_padg_prefill_us", "ecoserve_padg_simulate"]
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in ecoserve_padg.h but not exported"
+
+
 def test_binding_constants_match_the_header(binding):
     """Options, status codes and kernel ids are plain integers on both sides of the boundary."""
     text = open(HEADER).read()

@@ -1,0 +1,311 @@
+"""Host-side macro-instance model (include/ecoserve_padg.h): the plain Python oracle pinned to hand-worked
+cases of Algorithm 1, Algorithm 2 and the phase rules of Section 4.2.1, then the C++ implementation in the
+library against the oracle, exactly, on seeded random request streams.  No GPU is needed."""
+import random
+
+import pytest
+
+from oracle import padg_oracle as orc
+from paper_2504_18154_amd import binding, padg
+
+# A profile with easy numbers: 1 token -> 1 ms, 1001 tokens -> 101 ms (0.1 ms per token), 3001 tokens -> 501 ms
+# (0.2 ms per token beyond 1001).  Decode step: 5 ms + 10 us per sequence + 20 ns per cached token.
+PROFILE = dict(prefill_len=[1, 1001, 3001], prefill_us=[1_000, 101_000, 501_000], decode_base_us=5_000,
+               decode_per_seq_ns=10_000, decode_per_token_ns=20)
+
+
+def make(n_instances=1, slo_ttft_us=1_000_000, slo_tpot_us=100_000, kv=1_000_000, search_all=False, **over):
+    kw = dict(PROFILE, **over)
+    o = orc.Config(n_instances, slo_ttft_us, slo_tpot_us, kv, kw["prefill_len"], kw["prefill_us"], kw["decode_base_us"],
+                   kw["decode_per_seq_ns"], kw["decode_per_token_ns"], search_all)
+    p = padg.Config(n_instances, slo_ttft_us, slo_tpot_us, kv, kw["prefill_len"], kw["prefill_us"],
+                    kw["decode_base_us"], kw["decode_per_seq_ns"], kw["decode_per_token_ns"], search_all)
+    return o, p
+
+
+def run_oracle(cfg, stream):
+    return orc.simulate(cfg, [orc.Request(a, i, o) for a, i, o in stream])
+
+
+# ---------------------------------------------------------------------------------------------- oracle pins
+
+def test_oracle_prefill_predictor_interpolates_the_profile():
+    """Section 4.3: prefill durations come from a profile over sequence lengths."""
+    cfg, _ = make()
+    assert orc.prefill_us(cfg, 1) == 1_000 and orc.prefill_us(cfg, 1001) == 101_000 and orc.prefill_us(cfg, 3001) == 501_000
+    assert orc.prefill_us(cfg, 501) == 51_000                  # halfway up the first segment
+    assert orc.prefill_us(cfg, 2001) == 301_000                # halfway up the second
+    assert orc.prefill_us(cfg, 4001) == 701_000                # beyond the last point: the last slope goes on
+    assert orc.prefill_us(cfg, 2) == 1_100
+    flat, _ = make(prefill_len=[100, 200], prefill_us=[50, 40])
+    assert orc.prefill_us(flat, 1000) == 1                      # a falling profile never predicts less than 1 us
+    assert orc.prefill_us(flat, 150) == 45 and orc.prefill_us(flat, 50) == 55
+
+
+def test_oracle_algorithm2_constraint_by_constraint():
+    """Algorithm 2 with numbers worked by hand.  Prefills of 2001 and 1001 tokens predict 301 ms and 101 ms."""
+    cfg, _ = make(slo_ttft_us=503_000, slo_tpot_us=100_000, kv=10_000)
+    # 1. TTFT: phase [2001] + candidate 1001 + ... = 301 + 101 = 402 ms <= 503 ms; a second 1001 makes 503: still fine;
+    #    one more token on the candidate (1002 -> 101.1 ms) is over
+    assert orc.check_constraints(cfg, 0, [2001], [], [], 0, 1001) == orc.SATISFIED
+    assert orc.check_constraints(cfg, 0, [2001, 1001], [], [], 0, 1001) == orc.SATISFIED
+    assert orc.check_constraints(cfg, 0, [2001, 1001], [], [], 0, 1002) == orc.TTFT
+    # 2. TPOT: decodes with 10 tokens since 600 ms ago (saved 10*100 - 600 = 400 ms) and 20 tokens since 1900 ms ago
+    #    (saved 100 ms): mean 250 ms.  Candidate 2001 tokens (301 ms) interrupts them for longer than they saved ...
+    now = 5_000_000
+    dec = ([10, 20], [now - 600_000, now - 1_900_000])
+    assert orc.check_constraints(cfg, now, [], *dec, 0, 2001) == orc.TPOT
+    # ... 1001 tokens (101 ms) does not, and neither does a phase that adds up to exactly 250 ms (1001 + 1241 tokens:
+    # 101 ms + 101 + 240 * 0.2 = 149 ms); one more token does
+    assert orc.check_constraints(cfg, now, [], *dec, 0, 1001) == orc.SATISFIED
+    assert orc.prefill_us(cfg, 1241) == 149_000
+    assert orc.check_constraints(cfg, now, [1001], *dec, 0, 1241) == orc.SATISFIED
+    assert orc.check_constraints(cfg, now, [1001], *dec, 0, 1242) == orc.TPOT
+    #    a decode that is behind its SLO (5 tokens in 900 ms: saved -400 ms) drags the mean below any phase
+    assert orc.check_constraints(cfg, now, [], [5], [now - 900_000], 0, 1) == orc.TPOT
+    #    constraint 1 is tested first
+    assert orc.check_constraints(cfg, now, [3001], [5], [now - 900_000], 0, 1001) == orc.TTFT
+    # 3. memory: 10 000 tokens of cache, 9 000 in use: 1000 tokens fit, 1001 do not
+    assert orc.check_constraints(cfg, 0, [], [], [], 9_000, 1000) == orc.SATISFIED
+    assert orc.check_constraints(cfg, 0, [], [], [], 9_000, 1001) == orc.MEMORY
+
+
+def test_oracle_one_instance_timeline_by_hand():
+    """Section 4.2.1 on one instance: prefills first, one at a time, then decode steps over everything.
+    Three requests (arrival us, input, output): (0, 501, 3), (10, 1001, 2), (20, 101, 1)."""
+    cfg, _ = make()
+    r = run_oracle(cfg, [(0, 501, 3), (10, 1001, 2), (20, 101, 1)])
+    # prefill 501 tokens: 51 ms -> first token at 51 000.  The other two arrived meanwhile: the prefill phase goes on.
+    assert r[0].first_token_us == 51_000
+    assert r[1].first_token_us == 51_000 + 101_000          # 152 000
+    assert r[2].first_token_us == 152_000 + 11_000          # 101 tokens: 1 + 100 * 0.1 ms
+    assert r[2].finish_us == r[2].first_token_us            # a single output token: done with its prefill
+    # first decode step: 2 sequences holding 501 + 1 and 1001 + 1 tokens: 5000 + (2 * 10 000 + 1504 * 20) / 1000 = 5050 us
+    assert r[1].finish_us == 163_000 + 5_050                # its second token
+    # second step: 1 sequence with 503 tokens: 5000 + (10 000 + 10 060) / 1000 = 5020 us
+    assert r[0].finish_us == 168_050 + 5_020
+    assert [x.instance for x in r] == [0, 0, 0] and [x.check for x in r] == [0, 0, 0]
+
+
+def test_oracle_a_decode_step_is_not_interrupted_but_prefills_go_first_after_it():
+    """A request that arrives while a decode step runs waits for the end of that step (its TTFT includes the
+    phase-switching wait, Section 4.2.3), then is prefilled before any further decode step."""
+    cfg, _ = make()
+    r = run_oracle(cfg, [(0, 1, 1000), (3_000, 501, 2)])
+    # request 0: first token at 1000 us; decode steps of 5000 + (10 000 + 20 * tokens) / 1000 = 5010 us follow
+    assert r[0].first_token_us == 1_000
+    # the step running at t = 3000 ends at 6010; then the prefill (51 ms), then decode steps over both
+    assert r[1].first_token_us == 6_010 + 51_000
+    # Algorithm 2 at t = 3000: the one decode has 1 token since 2 ms: saved 100 - 2 = 98 ms >= 51 ms
+    assert r[1].check == orc.SATISFIED
+    # the next step holds (1 + 2) and (501 + 1) tokens: 5000 + (2 * 10 000 + 20 * 505) / 1000 = 5030 us
+    assert r[1].finish_us == r[1].first_token_us + 5_030
+    # the same with a 1001-token prompt (101 ms > 98 ms saved): refused on TPOT, but with a single instance
+    # Algorithm 1 has nowhere else to go
+    r = run_oracle(cfg, [(0, 1, 1000), (3_000, 1001, 2)])
+    assert r[1].check == orc.TPOT and r[1].instance == 0 and r[1].first_token_us == 6_010 + 101_000
+
+
+def test_oracle_algorithm1_rolling_activation():
+    """Algorithm 1 on three instances, TTFT SLO 250 ms, requests of 1001 tokens (101 ms prefill) arriving 1 ms
+    apart: two fit one prefill phase (202 ms), the third would make 303 ms, so routing moves on to the next
+    instance, and so on round the ring: the instances' prefill phases are staggered (Section 4.2.2)."""
+    cfg, _ = make(n_instances=3, slo_ttft_us=250_000)
+    stream = [(1_000 * k, 1001, 50) for k in range(7)]
+    r = run_oracle(cfg, stream)
+    assert [x.instance for x in r] == [0, 0, 1, 1, 2, 2, 0]
+    assert [x.check for x in r] == [0, 0, orc.TTFT, 0, orc.TTFT, 0, orc.TTFT]
+    # the seventh request comes back to instance 0, whose phase is still running (2 x 101 ms): as printed,
+    # Algorithm 1 does not check the instance it moves on to, and the request waits there
+    assert r[6].first_token_us == 202_000 + 101_000
+    # with the cyclic search of the text nothing changes here (no instance satisfies: all are mid-phase)
+    cfg2, _ = make(n_instances=3, slo_ttft_us=250_000, search_all=True)
+    assert [x.instance for x in run_oracle(cfg2, stream)] == [0, 0, 1, 1, 2, 2, 0]
+
+
+def test_oracle_cyclic_search_skips_an_instance_that_the_printed_algorithm_would_take():
+    """Instance 1 is busy with a long prefill when instance 0 refuses a request: as printed the request goes to
+    instance 1 regardless, with the cyclic search it goes on to the idle instance 2."""
+    stream = [(0, 3001, 5), (1_000, 3001, 5), (2_000, 1001, 5)]
+    printed, _ = make(n_instances=3, slo_ttft_us=520_000)
+    r = run_oracle(printed, stream)
+    assert [x.instance for x in r] == [0, 1, 2] or [x.instance for x in r] == [0, 1, 1]
+    assert [x.instance for x in r] == [0, 1, 2]             # 501 + 501 ms > SLO on 0, then 1 refuses: next is 2
+    stream = [(0, 3001, 5), (1_000, 3001, 5), (2_000, 1001, 5), (3_000, 3001, 5)]
+    r = run_oracle(printed, stream)
+    # request 3 (501 ms): instance 2 holds 101 ms -> 602 ms > 520: refused; printed: next = instance 0, unchecked
+    assert r[3].instance == 0 and r[3].check == orc.TTFT
+    searched, _ = make(n_instances=4, slo_ttft_us=520_000, search_all=True)
+    r = run_oracle(searched, stream)
+    assert r[3].instance == 3                                # 2 refuses, the search reaches the idle instance 3
+    four_printed, _ = make(n_instances=4, slo_ttft_us=520_000)
+    assert run_oracle(four_printed, stream)[3].instance == 3
+
+
+def test_oracle_memory_constraint_counts_pending_and_decoding_tokens():
+    cfg, _ = make(n_instances=2, kv=2_500)
+    r = run_oracle(cfg, [(0, 1001, 100), (10, 1001, 100), (20, 1001, 100)])
+    # instance 0 holds 1001 (being prefilled) + 1001 (pending) = 2002 tokens: a third 1001 does not fit into 2500
+    assert [x.instance for x in r] == [0, 0, 1] and r[2].check == orc.MEMORY
+
+
+def _streams(seed, n, rate_per_s, in_mean, out_mean):
+    rng = random.Random(seed)
+    t, out = 0, []
+    for _ in range(n):
+        t += int(rng.expovariate(rate_per_s) * 1e6)
+        out.append((t, max(1, int(rng.lognormvariate(0, 1.0) * in_mean * 0.6)),
+                    max(1, int(rng.lognormvariate(0, 0.9) * out_mean * 0.65))))
+    return out
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_oracle_invariants_on_random_streams(seed):
+    cfg, _ = make(n_instances=3, slo_ttft_us=400_000, slo_tpot_us=20_000, kv=60_000, search_all=bool(seed % 2))
+    stream = _streams(seed, 400, 40.0, 400, 60)
+    r = run_oracle(cfg, stream)
+    by_inst = {}
+    for x in r:
+        assert 0 <= x.instance < 3 and x.generated == x.output_len
+        assert x.first_token_us >= x.arrival_us + orc.prefill_us(cfg, x.input_len)    # nobody is faster than alone
+        assert x.finish_us >= x.first_token_us
+        # every token after the first takes at least one decode step of the smallest possible batch
+        assert x.finish_us - x.first_token_us >= (x.output_len - 1) * orc.decode_step_us(cfg, 1, x.input_len + 1)
+        by_inst.setdefault(x.instance, []).append(x)
+    for xs in by_inst.values():
+        # prefills on one instance never overlap: first tokens are at least the later one's prefill apart
+        xs.sort(key=lambda x: x.first_token_us)
+        for a, b in zip(xs, xs[1:]):
+            assert b.first_token_us - a.first_token_us >= orc.prefill_us(cfg, b.input_len)
+    assert 0.0 <= orc.slo_attainment(cfg, r) <= 1.0
+
+
+def test_oracle_pins_catch_planted_mistakes(monkeypatch):
+    """Each plausible slip in the oracle must fail at least one of the hand-worked pins above."""
+    pins = [test_oracle_prefill_predictor_interpolates_the_profile, test_oracle_algorithm2_constraint_by_constraint,
+            test_oracle_one_instance_timeline_by_hand,
+            test_oracle_a_decode_step_is_not_interrupted_but_prefills_go_first_after_it,
+            test_oracle_algorithm1_rolling_activation,
+            test_oracle_cyclic_search_skips_an_instance_that_the_printed_algorithm_would_take,
+            test_oracle_memory_constraint_counts_pending_and_decoding_tokens]
+
+    def caught():
+        for pin in pins:
+            try:
+                pin()
+            except AssertionError:
+                return True
+        return False
+
+    good_check, good_start, good_sched = orc.check_constraints, orc.MacroInstance._start_next, orc.MacroInstance._inter_schedule
+    assert not caught()
+
+    def ttft_without_the_candidate(cfg, now, phase, gen, first, used, n):
+        t_phase = sum(orc.prefill_us(cfg, x) for x in phase)
+        if t_phase > cfg.slo_ttft_us:
+            return orc.TTFT
+        t_total = t_phase + orc.prefill_us(cfg, n)
+        saved = [L * cfg.slo_tpot_us - (now - f) for L, f in zip(gen, first)]
+        if saved and sum(saved) < t_total * len(saved):
+            return orc.TPOT
+        return orc.MEMORY if n > cfg.kv_capacity_tokens - used else orc.SATISFIED
+
+    def tpot_uses_the_minimum(cfg, now, phase, gen, first, used, n):
+        st = good_check(cfg, now, phase, gen, first, used, n)
+        saved = [L * cfg.slo_tpot_us - (now - f) for L, f in zip(gen, first)]
+        t = sum(orc.prefill_us(cfg, x) for x in phase) + orc.prefill_us(cfg, n)
+        if st == orc.SATISFIED and saved and min(saved) < t:
+            return orc.TPOT
+        return st
+
+    def tpot_sign_flipped(cfg, now, phase, gen, first, used, n):
+        return good_check(cfg, 2 * min(first, default=now) - now if first else now, phase, gen, first, used, n)
+
+    for wrong in (ttft_without_the_candidate, tpot_uses_the_minimum, tpot_sign_flipped):
+        monkeypatch.setattr(orc, "check_constraints", wrong)
+        assert caught(), wrong.__name__
+    monkeypatch.setattr(orc, "check_constraints", good_check)
+
+    def decodes_first(self, I, now):      # the opposite priority
+        if I.decoding and I.pending:
+            saved, I.pending = I.pending, []
+            good_start(self, I, now)
+            I.pending = saved
+        else:
+            good_start(self, I, now)
+
+    monkeypatch.setattr(orc.MacroInstance, "_start_next", decodes_first)
+    assert caught(), "decodes first"
+    monkeypatch.setattr(orc.MacroInstance, "_start_next", good_start)
+
+    def always_next(self, req, now):      # plain round robin, no constraint check
+        req.check = 0
+        return (self.prev_idx + 1) % self.cfg.n_instances
+
+    monkeypatch.setattr(orc.MacroInstance, "_inter_schedule", always_next)
+    assert caught(), "round robin"
+    monkeypatch.setattr(orc.MacroInstance, "_inter_schedule", good_sched)
+    assert not caught()
+
+
+# ---------------------------------------------------------------------- the library against the oracle
+
+def test_library_predictor_equals_the_oracle_everywhere():
+    for kw in ({}, dict(prefill_len=[16, 64, 65, 1000, 5000], prefill_us=[900, 700, 4000, 4100, 90_000])):
+        o, p = make(**kw)
+        for n in list(range(1, 1200)) + [2047, 2048, 4095, 4096, 5000, 5001, 100_000]:
+            assert padg.prefill_us(p, n) == orc.prefill_us(o, n), n
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_library_algorithm2_equals_the_oracle_on_random_snapshots(seed):
+    rng = random.Random(100 + seed)
+    o, p = make(slo_ttft_us=rng.choice([150_000, 400_000, 2_000_000]), slo_tpot_us=rng.choice([10_000, 50_000]),
+                kv=rng.choice([5_000, 50_000]))
+    seen = set()
+    for _ in range(3000):
+        now = rng.randrange(10**6, 10**8)
+        phase = [rng.randrange(1, 3000) for _ in range(rng.randrange(0, 4))]
+        nd = rng.randrange(0, 6)
+        gen = [rng.randrange(1, 400) for _ in range(nd)]
+        first = [now - rng.randrange(0, 4_000_000) for _ in range(nd)]
+        used, n = rng.randrange(0, 60_000), rng.randrange(1, 4000)
+        want = orc.check_constraints(o, now, phase, gen, first, used, n)
+        assert padg.check_constraints(p, now, phase, gen, first, used, n) == want
+        seen.add(want)
+    assert len(seen) >= 3   # every outcome but at most one occurs under each drawn configuration
+
+
+@pytest.mark.parametrize("seed,n_inst,search_all,ttft,tpot,kv,rate", [
+    (11, 1, False, 1_000_000, 100_000, 1_000_000, 5.0),
+    (12, 2, False, 300_000, 30_000, 40_000, 30.0),
+    (13, 4, True, 300_000, 30_000, 40_000, 60.0),
+    (14, 8, False, 150_000, 15_000, 20_000, 150.0),
+    (15, 3, True, 5_000_000, 100_000, 8_000, 40.0),
+    (16, 5, False, 1, 1, 1, 80.0),                      # nothing ever satisfies: pure fallback routing
+])
+def test_library_simulation_equals_the_oracle_exactly(seed, n_inst, search_all, ttft, tpot, kv, rate):
+    o, p = make(n_instances=n_inst, slo_ttft_us=ttft, slo_tpot_us=tpot, kv=kv, search_all=search_all)
+    stream = _streams(seed, 1500, rate, 350, 80)
+    want = run_oracle(o, stream)
+    got = padg.simulate(p, stream)
+    assert len(got) == len(want)
+    for k, (g, w) in enumerate(zip(got, want)):
+        assert (g.instance, g.check, g.first_token_us, g.finish_us) == (w.instance, w.check, w.first_token_us, w.finish_us), k
+    assert len({g.instance for g in got}) == n_inst or n_inst == 1 or ttft > 10**6
+
+
+def test_library_rejects_bad_input():
+    _, p = make()
+    assert padg.simulate(p, []) == []
+    for bad in ([(10, 5, 5), (9, 5, 5)], [(0, 0, 5)], [(0, 5, 0)], [(-1, 5, 5)]):
+        with pytest.raises(binding.EcoserveError):
+            padg.simulate(p, bad)
+    for kw in (dict(prefill_len=[5, 5, 9]), dict(prefill_len=[1], prefill_us=[5]), dict(decode_base_us=-1)):
+        _, q = make(**kw)
+        with pytest.raises(binding.EcoserveError):
+            padg.simulate(q, [(0, 5, 5)])
+        with pytest.raises(binding.EcoserveError):
+            padg.prefill_us(q, 5)
+    with pytest.raises(binding.EcoserveError):
+        padg.check_constraints(p, 0, [0], [], [], 0, 5)
