@@ -1,0 +1,203 @@
+"""SLO attainment and goodput of a PaDG macro instance built from MI355X instances, from measured step times.
+
+    python -m paper_2504_18154_amd.padg_goodput [--instances 4] [--requests 4000] [--datasets sharegpt,alpaca,longbench]
+
+What the paper reports end to end (Section 5.2: goodput = the request rate a system sustains with 90% of the
+requests inside both SLOs) needs datasets, trained weights and a cluster.  What can be measured here is the
+time profile of one instance -- one MI355X holding the whole 30B-scale model -- and from it the macro-instance
+model of include/ecoserve_padg.h (Algorithm 1, Algorithm 2, temporal disaggregation) gives the same quantity
+for synthetic request streams shaped like Table 4's datasets, with Table 4's SLOs.
+
+Profile, measured on the GPU at hand (step 1):
+  * prefill of one request of n tokens, n over a grid: per layer kv_append + attn_prefill of this library
+    plus the layer's dense projections (Eq. 1, Eq. 3) as library GEMMs through torch.matmul on random weights
+    (hidden = Hq * D, intermediate 27648: a 31 B-parameter model with the benchmark's head shape), times the
+    number of layers;
+  * one decode step over b sequences with t cached tokens, over a grid of (b, t): per layer kv_append (one
+    token each) + attn_decode + the same projections for b tokens, times the layers; a least-squares fit
+    gives base + per-sequence + per-token costs.
+Simulation (step 2, host only): Poisson arrivals, lengths from workloads.table4_lengths, a sweep over request
+rates; prints one JSON line per dataset with the attainment curve and the goodput at 90%.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+SLO = {"alpaca": (1_000_000, 100_000), "sharegpt": (5_000_000, 100_000), "longbench": (15_000_000, 100_000)}  # Table 4
+INTERMEDIATE = 27648
+HBM_BYTES = 288e9
+
+
+def measure_profile(model, layers: int):
+    """Returns (prefill_len, prefill_us, decode_base_us, decode_per_seq_ns, decode_per_token_ns, details)."""
+    import torch
+
+    from . import binding
+    from . import workloads as wl
+
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(0)
+    H = model.Hq * model.D
+    qkv_w = torch.randn(H, (model.Hq + 2 * model.Hkv) * model.D, device=dev).to(torch.bfloat16) * 0.02
+    o_w = torch.randn(H, H, device=dev).to(torch.bfloat16) * 0.02
+    gu_w = torch.randn(H, 2 * INTERMEDIATE, device=dev).to(torch.bfloat16) * 0.02
+    d_w = torch.randn(INTERMEDIATE, H, device=dev).to(torch.bfloat16) * 0.02
+    i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=dev)
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps   # us
+
+    def dense(x):
+        """The layer's projections around attention, Eq. 1 and Eq. 3 (gated feed-forward), as library GEMMs."""
+        qkv = (x @ qkv_w).unflatten(1, (model.Hq + 2 * model.Hkv, model.D))
+        return qkv
+
+    def dense_tail(attn_out):
+        y = attn_out.flatten(1) @ o_w
+        gu = y @ gu_w
+        return (torch.nn.functional.silu(gu[:, :INTERMEDIATE]) * gu[:, INTERMEDIATE:]) @ d_w
+
+    prefill_len, prefill_us, details = [], [], {"prefill": [], "decode": []}
+    for n in (16, 64, 256, 1024, 2048, 4096):
+        pb = wl.prefill_batch(model, [n], 900 + n)
+        ctx = binding.Context(model.Hq, model.Hkv, model.D, pb.num_blocks, "bf16", 1, pb.block_table.shape[1])
+        kc, vc = ctx.new_cache(fill_bits=0)
+        x = wl.randn((n, H), "bf16", 1, device=dev)
+        out = torch.empty((n, model.Hq, model.D), dtype=torch.bfloat16, device=dev)
+        cu, cb, bt = i32(pb.cu_q), i32(pb.ctx_before), i32(pb.block_table)
+
+        def layer():
+            qkv = dense(x)
+            q, k, v = qkv[:, :model.Hq], qkv[:, model.Hq:model.Hq + model.Hkv], qkv[:, model.Hq + model.Hkv:]
+            ctx.kv_append_strided(kc, vc, k, v, cu, cb, bt, max_new_len=n)
+            ctx.attn_prefill_strided(q, kc, vc, cu, cb, bt, out, max_q_len=n)
+            dense_tail(out)
+
+        us = timed(layer, 20) * layers
+        prefill_len.append(n)
+        prefill_us.append(int(round(us)))
+        details["prefill"].append({"tokens": n, "us": us})
+        ctx.close()
+
+    rows, ys = [], []
+    for b, mean_ctx in ((16, 512), (64, 512), (256, 512), (64, 2048), (256, 2048), (512, 1024), (128, 4096)):
+        db = wl.decode_batch(model, b, mean_ctx, mean_ctx, 800 + b)
+        ctx = binding.Context(model.Hq, model.Hkv, model.D, db.num_blocks, "bf16", db.B, db.block_table.shape[1])
+        ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
+        n_el = db.num_blocks * model.Hkv * model.bs * model.D
+        kc = torch.randn(n_el, device=dev).to(torch.bfloat16)
+        vc = torch.randn(n_el, device=dev).to(torch.bfloat16)
+        x = wl.randn((b, H), "bf16", 2, device=dev)
+        out = torch.empty((b, model.Hq, model.D), dtype=torch.bfloat16, device=dev)
+        bt, cl = i32(db.block_table), i32(db.ctx_len)
+        cu, before = i32(np.arange(b + 1)), i32(db.ctx_len - 1)
+
+        def layer():
+            qkv = dense(x)
+            q, k, v = qkv[:, :model.Hq], qkv[:, model.Hq:model.Hq + model.Hkv], qkv[:, model.Hq + model.Hkv:]
+            ctx.kv_append_strided(kc, vc, k, v, cu, before, bt, max_new_len=1)
+            ctx.attn_decode_strided(q, kc, vc, bt, cl, out, db.max_ctx_len)
+            dense_tail(out)
+
+        us = timed(layer, 50) * layers
+        t = int(db.ctx_len.sum())
+        rows.append([1.0, b, t])
+        ys.append(us)
+        details["decode"].append({"batch": b, "tokens": t, "us": us})
+        ctx.close()
+    coef, *_ = np.linalg.lstsq(np.asarray(rows), np.asarray(ys), rcond=None)
+    base, per_seq, per_tok = (max(float(c), 0.0) for c in coef)
+    for d, row in zip(details["decode"], rows):
+        d["fit_us"] = base + per_seq * row[1] + per_tok * row[2]
+    return prefill_len, prefill_us, int(round(base)), int(round(per_seq * 1000)), int(round(per_tok * 1000)), details
+
+
+def poisson_stream(dataset: str, n: int, rate_per_s: float, seed: int):
+    from . import workloads as wl
+    rng = wl.rng_for(seed)
+    n_in, n_out = wl.table4_lengths(dataset, rng, n)
+    t = np.cumsum(rng.exponential(1e6 / rate_per_s, size=n)).astype(np.int64)
+    return [(int(a), int(i), int(o)) for a, i, o in zip(t, n_in, n_out)]
+
+
+def attainment(cfg_kw: dict, stream, slo) -> float:
+    from . import padg
+    cfg = padg.Config(**cfg_kw)
+    res = padg.simulate(cfg, stream)
+    ok = 0
+    for (arrival, _, n_out), r in zip(stream, res):
+        tpot_ok = n_out == 1 or (r.finish_us - r.first_token_us) <= slo[1] * (n_out - 1)
+        ok += (r.first_token_us - arrival) <= slo[0] and tpot_ok
+    return ok / len(stream)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--instances", type=int, default=4)
+    ap.add_argument("--requests", type=int, default=4000)
+    ap.add_argument("--datasets", default="alpaca,sharegpt,longbench")
+    ap.add_argument("--profile-json", default="", help="reuse a profile printed by an earlier run instead of measuring")
+    args = ap.parse_args()
+    from . import workloads as wl
+    model = wl.M30B
+    if args.profile_json:
+        prof = json.loads(args.profile_json)
+    else:
+        plen, pus, base, per_seq, per_tok, details = measure_profile(model, model.layers)
+        prof = {"prefill_len": plen, "prefill_us": pus, "decode_base_us": base, "decode_per_seq_ns": per_seq,
+                "decode_per_token_ns": per_tok, "details": details}
+    params = model.layers * (model.Hq * model.D * ((model.Hq + 2 * model.Hkv) * model.D + model.Hq * model.D)
+                             + 3 * model.Hq * model.D * INTERMEDIATE)
+    kv_tokens = int((HBM_BYTES * 0.9 - 2 * params) / (model.layers * model.kv_bytes_per_token_layer))
+    print(json.dumps({"profile": prof, "model_parameters": params, "kv_capacity_tokens": kv_tokens}), flush=True)
+    for ds in args.datasets.split(","):
+        slo = SLO[ds]
+        base_kw = dict(n_instances=args.instances, slo_ttft_us=slo[0], slo_tpot_us=slo[1], kv_capacity_tokens=kv_tokens,
+                       prefill_len=prof["prefill_len"], prefill_us=prof["prefill_us"],
+                       decode_base_us=prof["decode_base_us"], decode_per_seq_ns=prof["decode_per_seq_ns"],
+                       decode_per_token_ns=prof["decode_per_token_ns"])
+        line = {"dataset": ds, "instances": args.instances, "slo_ttft_s": slo[0] / 1e6, "slo_tpot_ms": slo[1] / 1e3}
+        for name, search_all in (("algorithm1_as_printed", False), ("algorithm1_cyclic_search", True)):
+            kw = dict(base_kw, search_all=search_all)
+            # bracket the 90% point: double the rate until attainment drops below 0.9, then bisect
+            lo, hi, curve = 0.0, 1.0, []
+            while hi < 1e5:
+                a = attainment(kw, poisson_stream(ds, args.requests, hi, 77), slo)
+                curve.append((hi, a))
+                if a < 0.9:
+                    break
+                lo, hi = hi, hi * 2
+            for _ in range(12):
+                mid = 0.5 * (lo + hi)
+                a = attainment(kw, poisson_stream(ds, args.requests, mid, 77), slo)
+                curve.append((mid, a))
+                if a >= 0.9:
+                    lo = mid
+                else:
+                    hi = mid
+            line[name] = {"goodput_req_per_s": lo, "goodput_per_instance": lo / args.instances,
+                          "curve": sorted((round(r, 3), round(a, 4)) for r, a in curve)}
+        print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
