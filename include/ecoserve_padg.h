@@ -1,11 +1,11 @@
 /*
  * ecoserve_padg.h -- host-side model of one EcoServe macro instance: the
- * inter-instance scheduling of Section 4.3 (Algorithm 1, InterSchedule, and
+ * inter-instance scheduling of Section 3.4 (Algorithm 1, InterSchedule, and
  * Algorithm 2, CheckConstraints) over instances that each follow the
- * temporal disaggregation of Section 4.2.1 (one phase at a time, prefills
+ * temporal disaggregation of Section 3.2.1 (one phase at a time, prefills
  * first), driven by measured step durations.  It turns kernel timings into
  * the paper's currency: TTFT, TPOT and SLO attainment of a request stream
- * (Section 4.2.3, Section 5.1).  No GPU is involved; everything is host
+ * (Section 3.3, Section 4.1).  No GPU is involved; everything is host
  * memory and every pointer is a host pointer owned by the caller.
  *
  * All times are integer microseconds, all sizes are tokens, so that the
@@ -36,7 +36,7 @@
  *  Durations: prefill of a request with n input tokens = piecewise-linear
  *  interpolation through the profile points (extrapolating the first / last
  *  segment outside them, never below 1), the predictor Algorithm 2 asks for
- *  (Section 4.3: profiled in advance for sequences of various lengths);
+ *  (Section 3.4: profiled in advance for sequences of various lengths);
  *  decode step over b sequences holding t cached tokens in total =
  *  decode_base_us + (decode_per_seq_ns * b + decode_per_token_ns * t) / 1000.
  *
@@ -58,7 +58,7 @@
  *  Algorithm 1: try the instance the previous request was routed to (instance
  *  0 for the first request); if Algorithm 2 is not satisfied, take the next
  *  instance cyclically -- as printed, without checking it (search_all == 0),
- *  or, as the text of Section 4.3 reads, checking each following instance in
+ *  or, as the text of Section 3.4 reads, checking each following instance in
  *  turn and falling back to the next one only if none satisfies
  *  (search_all == 1).
  */

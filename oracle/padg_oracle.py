@@ -1,10 +1,10 @@
 """Plain Python model of one EcoServe macro instance (test infrastructure only).
 
 Written from the paper, step by step and in its notation, with no attempt at speed:
-Section 4.2.1 (temporal disaggregation: an instance runs one phase at a time and puts
-prefills first), Section 4.3 (Algorithm 1, InterSchedule; Algorithm 2, CheckConstraints;
+Section 3.2.1 (temporal disaggregation: an instance runs one phase at a time and puts
+prefills first), Section 3.4 (Algorithm 1, InterSchedule; Algorithm 2, CheckConstraints;
 the prefill-duration predictor profiled over sequence lengths) and the metrics of Sections
-4.2.3 / 5.1 (TTFT including the phase-switching wait, TPOT measured from the first token,
+3.3 / 4.1 (TTFT including the phase-switching wait, TPOT measured from the first token,
 SLO attainment).  Integer microseconds and token counts throughout, so results are exact.
 
 Only tests/ may import this module; the product is the C++ implementation behind
@@ -46,7 +46,7 @@ class Request:
 
 
 def prefill_us(cfg: Config, n: int) -> int:
-    """Section 4.3: the prefill duration of a request is predicted from a profile over sequence lengths.
+    """Section 3.4: the prefill duration of a request is predicted from a profile over sequence lengths.
     Linear interpolation between neighbouring profile points, the outer segments extended outwards."""
     L, U = cfg.prefill_len, cfg.prefill_us
     k = 0
@@ -96,7 +96,7 @@ class MacroInstance:
         self.inst = [Instance() for _ in range(cfg.n_instances)]
         self.prev_idx = 0
 
-    # ---- one instance: Section 4.2.1 -------------------------------------------------------------
+    # ---- one instance: Section 3.2.1 -------------------------------------------------------------
     def _start_next(self, I: Instance, now: int):
         if I.pending:                       # prefills first
             r = I.pending.pop(0)
@@ -179,8 +179,8 @@ def simulate(cfg: Config, reqs: List[Request]) -> List[Request]:
 
 
 def slo_attainment(cfg: Config, reqs: Sequence[Request]) -> float:
-    """Share of requests that meet both SLOs (Section 5.1): TTFT = first token - arrival (phase-switching
-    wait included, Section 4.2.3), TPOT = (finish - first token) / (output tokens after the first)."""
+    """Share of requests that meet both SLOs (Section 4.1): TTFT = first token - arrival (phase-switching
+    wait included, Section 3.3), TPOT = (finish - first token) / (output tokens after the first)."""
     ok = 0
     for r in reqs:
         ttft = r.first_token_us - r.arrival_us

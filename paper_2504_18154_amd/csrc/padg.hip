@@ -1,11 +1,11 @@
 // Host-side model of one EcoServe macro instance (no device code in this file).
 //
-// Section 4.2.1 of the paper: every instance runs one phase at a time for an extended duration
-// and puts prefills first.  Section 4.3: Algorithm 1 (InterSchedule) routes each request to the
+// Section 3.2.1 of the paper: every instance runs one phase at a time for an extended duration
+// and puts prefills first.  Section 3.4: Algorithm 1 (InterSchedule) routes each request to the
 // instance that took the previous one while Algorithm 2 (CheckConstraints: the prefill phase must
 // fit the TTFT SLO, the interrupted decodes must have saved enough TPOT on average, the KV cache
 // must fit) allows it, else moves on cyclically -- which staggers the instances' prefill phases
-// (rolling activation, Section 4.2.2).  The exact rules of the model are stated in
+// (rolling activation, Section 3.2.2).  The exact rules of the model are stated in
 // include/ecoserve_padg.h; this file is their only implementation on the product side.
 //
 // Requests are kept in flat arrays and referred to by index; an instance is three index lists
@@ -41,7 +41,7 @@ bool config_ok(const ecoserve_padg_config* c) {
   return true;
 }
 
-// Section 4.3: the predictor profiled over sequence lengths
+// Section 3.4: the predictor profiled over sequence lengths
 int64_t predict_prefill(const ecoserve_padg_config& c, int32_t n) {
   const int32_t* L = c.prefill_len;
   const int64_t* U = c.prefill_us;

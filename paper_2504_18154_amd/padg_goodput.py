@@ -2,7 +2,7 @@
 
     python -m paper_2504_18154_amd.padg_goodput [--instances 4] [--requests 4000] [--datasets sharegpt,alpaca,longbench]
 
-What the paper reports end to end (Section 5.2: goodput = the request rate a system sustains with 90% of the
+What the paper reports end to end (Section 4.2: goodput = the request rate a system sustains with 90% of the
 requests inside both SLOs) needs datasets, trained weights and a cluster.  What can be measured here is the
 time profile of one instance -- one MI355X holding the whole 30B-scale model -- and from it the macro-instance
 model of include/ecoserve_padg.h (Algorithm 1, Algorithm 2, temporal disaggregation) gives the same quantity

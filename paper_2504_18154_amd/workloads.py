@@ -52,7 +52,7 @@ class ModelShape:
 TINY = ModelShape("tiny-fp32", Hq=4, Hkv=2, D=64, layers=1, dtype="f32")
 M30B = ModelShape("30B-scale", Hq=40, Hkv=8, D=128, layers=64, dtype="bf16")
 M70B = ModelShape("70B-scale", Hq=64, Hkv=8, D=128, layers=80, dtype="bf16")
-# multi-head attention, no K/V sharing: the head shape of the third model of the paper's evaluation (Section 5.1)
+# multi-head attention, no K/V sharing: the head shape of the third model of the paper's evaluation (Section 4.1)
 M30B_MHA = ModelShape("30B-scale-MHA", Hq=52, Hkv=52, D=128, layers=60, dtype="bf16")
 
 
@@ -85,7 +85,7 @@ TABLE4 = {"alpaca": (20.63, 17.0, 163.80, 119.0), "sharegpt": (343.76, 148.0, 23
 def table4_lengths(name: str, rng, n: int, max_len: int = 4096):
     """(input, output) token counts shaped like one dataset of Table 4: lognormal with the table's average
     and median where the average exceeds the median (sigma^2 = 2 ln(avg / median)), else (LongBench inputs)
-    normal around the average with a third of it as deviation; inputs are cut at `max_len` as in Section 5.1."""
+    normal around the average with a third of it as deviation; inputs are cut at `max_len` as in Section 4.1."""
     in_avg, in_med, out_avg, out_med = TABLE4[name]
 
     def draw(avg, med, lo, hi):

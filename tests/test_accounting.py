@@ -76,7 +76,7 @@ def test_workload_recipes_are_seeded_and_in_range():
 
 def test_table4_shaped_lengths_reproduce_the_table():
     """The synthetic stand-ins for the paper's datasets have Table 4's averages and medians
-    (inputs are cut at 4096 tokens as in Section 5.1, which lowers ShareGPT's input average a little)."""
+    (inputs are cut at 4096 tokens as in Section 4.1, which lowers ShareGPT's input average a little)."""
     for name, (in_avg, in_med, out_avg, out_med) in wl.TABLE4.items():
         n_in, n_out = wl.table4_lengths(name, wl.rng_for(5), 40000)
         assert n_in.min() >= 1 and n_in.max() <= 4096 and n_out.min() >= 1

@@ -125,7 +125,7 @@ def test_bf16_decode_split_plans(model):
 
 def test_bf16_multi_head_attention_no_kv_sharing():
     """52 query heads with a K/V head each (G = 1): the head shape of the multi-head model of the
-    paper's evaluation (Section 5.1).  Prefill over ragged prompts, then decode steps on the grown
+    paper's evaluation (Section 4.1).  Prefill over ragged prompts, then decode steps on the grown
     contexts; decode arithmetic intensity is 1, the purest memory-bound case."""
     model = wl.ModelShape("mha", 52, 52, 128, 1, "bf16")
     q_len = [5, 130, 16, 257, 64, 1, 700]

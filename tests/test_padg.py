@@ -1,5 +1,5 @@
 """Host-side macro-instance model (include/ecoserve_padg.h): the plain Python oracle pinned to hand-worked
-cases of Algorithm 1, Algorithm 2 and the phase rules of Section 4.2.1, then the C++ implementation in the
+cases of Algorithm 1, Algorithm 2 and the phase rules of Section 3.2.1, then the C++ implementation in the
 library against the oracle, exactly, on seeded random request streams.  No GPU is needed."""
 import random
 
@@ -30,7 +30,7 @@ def run_oracle(cfg, stream):
 # ---------------------------------------------------------------------------------------------- oracle pins
 
 def test_oracle_prefill_predictor_interpolates_the_profile():
-    """Section 4.3: prefill durations come from a profile over sequence lengths."""
+    """Section 3.4: prefill durations come from a profile over sequence lengths."""
     cfg, _ = make()
     assert orc.prefill_us(cfg, 1) == 1_000 and orc.prefill_us(cfg, 1001) == 101_000 and orc.prefill_us(cfg, 3001) == 501_000
     assert orc.prefill_us(cfg, 501) == 51_000                  # halfway up the first segment
@@ -71,7 +71,7 @@ def test_oracle_algorithm2_constraint_by_constraint():
 
 
 def test_oracle_one_instance_timeline_by_hand():
-    """Section 4.2.1 on one instance: prefills first, one at a time, then decode steps over everything.
+    """Section 3.2.1 on one instance: prefills first, one at a time, then decode steps over everything.
     Three requests (arrival us, input, output): (0, 501, 3), (10, 1001, 2), (20, 101, 1)."""
     cfg, _ = make()
     r = run_oracle(cfg, [(0, 501, 3), (10, 1001, 2), (20, 101, 1)])
@@ -89,7 +89,7 @@ def test_oracle_one_instance_timeline_by_hand():
 
 def test_oracle_a_decode_step_is_not_interrupted_but_prefills_go_first_after_it():
     """A request that arrives while a decode step runs waits for the end of that step (its TTFT includes the
-    phase-switching wait, Section 4.2.3), then is prefilled before any further decode step."""
+    phase-switching wait, Section 3.3), then is prefilled before any further decode step."""
     cfg, _ = make()
     r = run_oracle(cfg, [(0, 1, 1000), (3_000, 501, 2)])
     # request 0: first token at 1000 us; decode steps of 5000 + (10 000 + 20 * tokens) / 1000 = 5010 us follow
@@ -109,7 +109,7 @@ def test_oracle_a_decode_step_is_not_interrupted_but_prefills_go_first_after_it(
 def test_oracle_algorithm1_rolling_activation():
     """Algorithm 1 on three instances, TTFT SLO 250 ms, requests of 1001 tokens (101 ms prefill) arriving 1 ms
     apart: two fit one prefill phase (202 ms), the third would make 303 ms, so routing moves on to the next
-    instance, and so on round the ring: the instances' prefill phases are staggered (Section 4.2.2)."""
+    instance, and so on round the ring: the instances' prefill phases are staggered (Section 3.2.2)."""
     cfg, _ = make(n_instances=3, slo_ttft_us=250_000)
     stream = [(1_000 * k, 1001, 50) for k in range(7)]
     r = run_oracle(cfg, stream)
