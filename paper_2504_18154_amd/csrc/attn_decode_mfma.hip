@@ -106,16 +106,25 @@ __device__ __forceinline__ void process_block(KVFrag& f, const bf16x8 (&qf)[4], 
   for (int dt = 0; dt < 8; ++dt) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(f.v[dt], pbits, acc[dt], 0, 0, 0);
 }
 
-// Exclusive prefix sums of the per-sequence block counts into LDS: pre[b] = blocks of
-// sequences 0..b-1, pre[B] = all; lens[b] = context length.  Called by all 256 threads.
+// A piece costs a wavefront several blocks' worth of time (its pipeline fill and drain, its result's
+// stores: a wavefront's end time rises by ~3 us with every piece in its chunk), and some chunks hold a
+// dozen pieces when others hold one.  So that equal chunks are equal work, every (sequence, K/V head) is
+// numbered with kPieceCost units in front of its blocks that stand for that cost and hold no data (in
+// units of a block's time, which differs between the kernel's two shapes).
+// (values from a sweep over 0..12 on five batch shapes: flat between 6 and 8 / 4 and 6, worse outside)
+constexpr int kPieceCostStream = 6;  // one wavefront per SIMD
+constexpr int kPieceCostShared = 4;  // two per SIMD: a block takes about twice as much of a wavefront's time
+
+// Exclusive prefix sums of the per-sequence unit counts (blocks + kPieceCost) into LDS: pre[b] = units
+// per K/V head of sequences 0..b-1, pre[B] = all; lens[b] = context length.  Called by all 256 threads.
 __device__ __forceinline__ void scan_block_counts(int* pre, int* lens, int* wsum, const int32_t* __restrict__ ctx_len,
-                                                  int B) {
+                                                  int B, int kPieceCost) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per = (B + kWaves * 64 - 1) / (kWaves * 64);
   const int b0 = tid * per;
   int local = 0;
   for (int i = 0; i < per; ++i)
-    if (b0 + i < B) local += (ctx_len[b0 + i] + 15) >> 4;
+    if (b0 + i < B) local += ((ctx_len[b0 + i] + 15) >> 4) + kPieceCost;
   int x = local;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -131,7 +140,7 @@ __device__ __forceinline__ void scan_block_counts(int* pre, int* lens, int* wsum
       const int L = ctx_len[b0 + i];
       lens[b0 + i] = L;
       pre[b0 + i] = run;
-      run += (L + 15) >> 4;
+      run += ((L + 15) >> 4) + kPieceCost;
     }
   if (tid == 0) pre[B] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
   __syncthreads();
@@ -186,7 +195,8 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
   __shared__ int s_c[8], s_cum[9];
   __shared__ __attribute__((aligned(16))) uint16_t s_new[kWaves][256];  // fused append: a token's K row, then its V row
   const long long t_start = wall_clock64();
-  scan_block_counts(pre, lens, wsum, ctx_len, B);
+  constexpr int kPieceCost = kWgsPerCu == 2 ? kPieceCostShared : kPieceCostStream;
+  scan_block_counts(pre, lens, wsum, ctx_len, B, kPieceCost);
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, quad = lane >> 4;
@@ -252,8 +262,9 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
   // previous piece is still streaming, so a change of piece costs one memory round trip
   // (the refill of the block pipeline) instead of three.
   struct Piece {
-    int b, g, blk0, n, nb, L;
-    long long seg_u0;
+    int b, g, blk0, n, nb, L;  // blocks [blk0, blk0 + n) of the nb blocks of (b, g); n == 0: the chunk ends before block 0
+    long long seg_u0;          // first unit of (b, g): kPieceCost cost units, then its blocks
+    long long u_stop;          // where the piece ends in the numbering (chunk end or end of (b, g))
   };
   auto locate = [&](long long u) {
     Piece p;
@@ -264,12 +275,14 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
       if (pre[mid] <= key) lo = mid; else hi = mid;
     }
     p.b = lo;
-    p.nb = pre[lo + 1] - pre[lo];
+    const int nu = pre[lo + 1] - pre[lo];  // units of one (sequence, head)
+    p.nb = nu - kPieceCost;
     const long long seq_u0 = (long long)pre[lo] * Hkv;
-    p.g = (int)((u - seq_u0) / p.nb);
-    p.seg_u0 = seq_u0 + (long long)p.g * p.nb;
-    p.blk0 = (int)(u - p.seg_u0);
-    p.n = (int)(min(u_end, p.seg_u0 + p.nb) - u);
+    p.g = (int)((u - seq_u0) / nu);
+    p.seg_u0 = seq_u0 + (long long)p.g * nu;
+    p.u_stop = min(u_end, p.seg_u0 + nu);
+    p.blk0 = max((int)(u - p.seg_u0) - kPieceCost, 0);
+    p.n = max((int)(p.u_stop - p.seg_u0) - kPieceCost, 0) - p.blk0;
     p.L = lens[lo];
     return p;
   };
@@ -295,7 +308,8 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
   load_q(qf, cur);
   int ids = load_ids(cur, 0);
   for (;;) {
-    const long long u_next = u + cur.n;
+    if (cur.n == 0) break;  // only the cost units of the next (sequence, head) are left in this chunk
+    const long long u_next = cur.u_stop;
     const bool has_next = u_next < u_end;
     Piece nxt = cur;
     bf16x8 qn[4];
@@ -404,7 +418,7 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
         }
         if (lse && quad == 0) lse[(size_t)cur.b * Hq + h] = (m + log2f(l)) * kLn2;
       } else {
-        const int split = gw - ch.owner(cur.seg_u0);
+        const int split = gw - ch.owner(cur.seg_u0 + kPieceCost);  // counted from the chunk that holds block 0
         const size_t slot = ((size_t)cur.b * Hq + h) * ws_splits + split;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
@@ -425,8 +439,8 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
     // For the merge kernel: a (sequence, K/V head) that starts in this chunk and runs on into later ones
     // is this chunk's last piece; its partial states are those of this wavefront and the following
     // n_split - 1.  Every cut (sequence, head) is reported exactly once, by the chunk it starts in.
-    const bool cut = cur.seg_u0 >= u_begin && cur.seg_u0 + cur.nb > u_end;
-    ws_cut[4 * gw] = cut ? ch.owner(cur.seg_u0 + cur.nb - 1) - gw + 1 : 0;
+    const bool cut = cur.n > 0 && cur.blk0 == 0 && cur.n < cur.nb;
+    ws_cut[4 * gw] = cut ? ch.owner(cur.seg_u0 + kPieceCost + cur.nb - 1) - gw + 1 : 0;
     ws_cut[4 * gw + 1] = cur.b;
     ws_cut[4 * gw + 2] = cur.g;
   }
@@ -493,9 +507,10 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
   const int h = blockIdx.x, b = blockIdx.y, g = h / G;
   if (xcd_speed && b * Hq + h < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, b * Hq + h);
   const Chunking ch = {ws_meta, ws_meta + 8};
-  const int p0 = ws_meta[kMetaPre + b], nb = ws_meta[kMetaPre + b + 1] - p0;
-  const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nb;
-  const int n_split = ch.owner(seg_u0 + nb - 1) - ch.owner(seg_u0) + 1;
+  constexpr int kPieceCost = kPieceCostStream;  // (a forced split runs the one-per-SIMD shape)
+  const int p0 = ws_meta[kMetaPre + b], nu = ws_meta[kMetaPre + b + 1] - p0;  // units: kPieceCost + blocks
+  const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nu;
+  const int n_split = ch.owner(seg_u0 + nu - 1) - ch.owner(seg_u0 + kPieceCost) + 1;
   if (n_split <= 1) return;  // written in final form by the decode kernel
   merge_partials(ws_acc, ws_ml, ((size_t)b * Hq + h) * ws_splits, n_split, out + ((size_t)b * Hq + h) * 128,
                  lse ? lse + (size_t)b * Hq + h : nullptr);
@@ -531,7 +546,7 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   if (split_tokens > 0) {
     // forced chunk size: the grid must cover the largest possible number of units
     c_forced = split_tokens / kBlockSize;
-    const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize);
+    const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize + kPieceCostStream);
     const long long waves = (u_max + c_forced - 1) / c_forced;
     n_wg = (int)((waves + kWaves - 1) / kWaves);
     share_in = nullptr;
