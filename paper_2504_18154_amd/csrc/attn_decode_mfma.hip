@@ -7,7 +7,8 @@
 //
 // Work decomposition ("flat" split-context).  A unit of work is one 16-token cache block
 // of one (sequence, K/V head): 4 KiB of K and 4 KiB of V serving all G query heads of the
-// group.  Units are numbered sequence-major, then K/V head, then logical block, and the
+// group.  Units are numbered sequence-major, then K/V head, then logical block (each
+// (sequence, head) preceded by a few empty units that stand for the fixed cost of a piece), and the
 // numbering is cut into equal chunks of C units, one chunk per wavefront of a persistent
 // grid (one workgroup of 4 wavefronts per CU: one wavefront per SIMD, which is also the oldest
 // and so never starved by the memory pipeline's oldest-first arbitration).  Context lengths live on the device, so every
