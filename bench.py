@@ -454,9 +454,11 @@ def main() -> int:
     if not args.no_probes:
         res["machine"] = {
             "hbm_read_GBps": binding.probe_hbm_read(4 << 30, reps=5),
+            "hbm_read_same_bytes_GBps": binding.probe_hbm_read(int(dec_bytes_layer) // 8192 * 8192, reps=20),
             "mfma_bf16_TFLOPs": binding.probe_mfma_bf16(False, reps=5),
             "mfma_bf16_random_operands_TFLOPs": binding.probe_mfma_bf16(True, reps=5),
-            "how": "after the timed region: 4 GiB read in 8 KiB pieces per wavefront, 16-byte loads; register-only 32x32x16 bf16 loop, "
+            "how": "after the timed region: 4 GiB (and as many bytes as one decode launch reads) read in 8 KiB pieces per "
+                   "wavefront, 16-byte non-temporal loads; register-only 32x32x16 bf16 loop, "
                    "4 wavefronts per SIMD, smooth and pseudo-random operands; 5 launches each after one untimed",
         }
     print(json.dumps(res))

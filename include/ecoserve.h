@@ -288,7 +288,9 @@ int ecoserve_attn_decode_append(ecoserve_ctx* ctx, const void* q, int64_t q_row_
  * ecoserve_probe_hbm_read: reads a buffer of `bytes` (a multiple of 8192, at
  *   least 1 MiB; use more than the 256 MiB last-level cache, e.g. 4 GiB) once
  *   per launch, each wavefront taking whole 8 KiB pieces with coalesced
- *   16-byte loads; *gb_per_s = bytes / mean launch time, in 1e9 B/s.
+ *   16-byte non-temporal loads (the fastest read pattern known to this
+ *   library, and the decode kernel's); *gb_per_s = bytes / mean launch time,
+ *   in 1e9 B/s.
  *   ECOSERVE_ENOMEM if the buffer cannot be allocated.
  * ecoserve_probe_mfma_bf16: a register-only loop of 32x32x16 bf16 matrix
  *   instructions, four wavefronts per SIMD; `random_operands` != 0 feeds every

@@ -59,15 +59,25 @@ struct KVFrag {
 // Every cached K/V byte is read once per launch and by one wavefront only, so the loads carry
 // the non-temporal hint: the caches then do not keep the lines, and the device streams them
 // faster (a plain read of the same bytes in the same 8 KiB pieces: 7.0-7.2 TB/s with the
-// hint against 6.0-6.4 TB/s without).
+// hint against 6.0-6.4 TB/s without).  They are buffer loads through a descriptor of the one
+// block (4 KiB of K, 4 KiB of V): the block's address is wavefront-uniform and lives in scalar
+// registers, the lanes' offsets are two constants, and a load the pipeline issues past the end
+// of a piece (`live` false) gets a descriptor of zero bytes, which the hardware answers with
+// zeros without touching memory (the address it holds is a valid block all the same).
+constexpr int kRsrcRaw = 0x00020000;  // untyped 32-bit data, no swizzle, no stride
+constexpr int kAuxNonTemporal = 2;
 __device__ __forceinline__ void load_block(KVFrag& f, const char* __restrict__ kbase, const char* __restrict__ vbase,
-                                           int lane, int col, int quad) {
+                                           bool live, int lane, int col, int quad) {
+  const int bytes = live ? 4096 : 0;
+  const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kbase), 0, bytes, kRsrcRaw);
+  const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vbase), 0, bytes, kRsrcRaw);
+  const int koff = lane * 16, voff = col * 32 + quad * 8;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
-    f.k[kk] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(kbase + kk * 1024 + lane * 16));
+    f.k[kk] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, koff + kk * 1024, 0, kAuxNonTemporal));
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt)
-    f.v[dt] = __builtin_nontemporal_load(reinterpret_cast<const s16x4*>(vbase + dt * 512 + col * 32 + quad * 8));
+    f.v[dt] = __builtin_bit_cast(s16x4, __builtin_amdgcn_raw_buffer_load_b64(rv, voff + dt * 512, 0, kAuxNonTemporal));
 }
 
 // One block's worth of work for one wavefront: scores, online softmax update, value
@@ -345,13 +355,14 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
       const int n = min(64, cur.n - base);
       const int my_id = ids;
       if (base + 64 < cur.n) ids = load_ids(cur, base + 64);  // ids of the following 64 blocks, early
-      // Register pipeline kDepth blocks deep.  Loads are issued unconditionally with the
-      // index clamped to the last block (a harmless re-read that hits in cache), so the
-      // number of loads in flight is the same on every path and waits stay precise.
+      // Register pipeline kDepth blocks deep.  Loads are issued unconditionally, those past the
+      // end of the piece as loads of nothing (index clamped to the last block, zero-byte
+      // descriptor), so the number of loads in flight is the same on every path and waits
+      // stay precise.
       auto issue = [&](KVFrag& f, int i) {
         const int ii = min(i, n - 1);
         const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, ii) * blk_stride + head_off;
-        load_block(f, k_cache + off, v_cache + off, lane, col, quad);
+        load_block(f, k_cache + off, v_cache + off, i < n, lane, col, quad);
       };
       auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // > 16 except in the sequence's last block
       // Fused append (k_new given): the sequence's newest token, slot t of its last block, is not in the

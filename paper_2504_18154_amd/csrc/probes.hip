@@ -31,8 +31,9 @@ __global__ __launch_bounds__(kProbeThreads) void probe_fill_kernel(u4* __restric
 }
 
 // Every 8 KiB piece of the buffer is read once, by one wavefront, as eight coalesced 16-byte
-// loads per lane (the access shape of a paged K/V block; grid-stride streaming measures some
-// 10% lower on this device).  Nothing is written unless the xor of all data hits one value.
+// loads per lane with the non-temporal hint (the access shape of a paged K/V block as the decode
+// kernel reads it; without the hint the same loop measures 10-12% lower on this device, and
+// grid-stride streaming lower still).  Nothing is written unless the xor of all data hits one value.
 __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const u4* __restrict__ src, size_t n_pieces,
                                                                     u4* __restrict__ sink) {
   const int lane = threadIdx.x & 63;
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const u4* __r
   for (size_t c = wave; c < n_pieces; c += n_waves) {
     const u4* p = src + c * (kProbePiece / 16);
 #pragma unroll
-    for (int k = 0; k < kProbePiece / (64 * 16); ++k) acc ^= p[k * 64 + lane];
+    for (int k = 0; k < kProbePiece / (64 * 16); ++k) acc ^= __builtin_nontemporal_load(&p[k * 64 + lane]);
   }
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u && acc.x == 0x9e3779b9u) sink[lane] = acc;
 }
@@ -152,10 +153,12 @@ int ecoserve_probe_hbm_read(int device, size_t bytes, int32_t reps, double* gb_p
   const size_t n_vec = bytes / 16;
   const dim3 grid((unsigned)(num_cu * 8)), block(kProbeThreads);
   hipLaunchKernelGGL(probe_fill_kernel, grid, block, 0, nullptr, buf, n_vec);
+  // one wavefront per SIMD, as the decode kernel runs (more wavefronts read 3-6% slower with these loads)
+  const dim3 read_grid((unsigned)num_cu);
   double ms = 0.0;
   const hipError_t e = time_launches(
-      [&] { hipLaunchKernelGGL(probe_read_kernel, grid, block, 0, nullptr, buf, bytes / kProbePiece, sink); }, reps,
-      &ms);
+      [&] { hipLaunchKernelGGL(probe_read_kernel, read_grid, block, 0, nullptr, buf, bytes / kProbePiece, sink); },
+      reps, &ms);
   (void)hipFree(buf);
   (void)hipFree(sink);
   if (e != hipSuccess) return ECOSERVE_EHIP;
