@@ -169,9 +169,10 @@ def main() -> int:
     ap.add_argument("--fused-qkv", action="store_true",
                     help="Q, K and V are slices of one row [Hq + 2 Hkv][D] per token (the output of a fused projection, "
                          "Eq. 1) and are read in place through the strided calls; default: three packed arrays")
-    ap.add_argument("--fused-append", action="store_true",
-                    help="decode phase: one call per layer that appends the new tokens inside the decode launch "
-                         "(default: kv_append and attn_decode as two calls)")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="decode phase: kv_append and attn_decode as two calls per layer (default: one call, "
+                         "ecoserve_attn_decode_append, which takes the new tokens from the new rows and stores them "
+                         "with its merge launch; same bits in cache and output)")
     ap.add_argument("--event-every", type=int, default=7,
                     help="bracket every n-th launch of each kernel with HIP events inside the timed region (an event pair "
                          "per launch delays the stream by several microseconds per layer; 1 = every launch)")
@@ -320,7 +321,7 @@ def main() -> int:
             for l in range(layers):
                 kc, vc = d_pools[l]
                 kn, vn = (d_knew0, d_vnew0) if l == 0 else (d_knew, d_vnew)
-                if args.fused_append:
+                if not args.separate_append:
                     dctx.attn_decode_append(d_q, kn, vn, kc, vc, d_bt, d_len, d_out[l], db.max_ctx_len)
                 else:
                     append(dctx)(kc, vc, kn, vn, d_cu, d_before, d_bt, max_new_len=1)
@@ -375,7 +376,7 @@ def main() -> int:
                         "block 16; append + attention per layer",
             "layers": layers, "phase": args.phase, "decode_shares": "equal" if args.equal_shares else "per-XCD, measured",
             "prefill_tile_list": "built once per step, shared by the layers",
-            "decode_append": "fused into the decode launch" if args.fused_append else "a launch of its own",
+            "decode_append": "a launch of its own" if args.separate_append else "fused into the decode call",
             "qkv_rows": "slices of fused rows [tokens, Hq + 2 Hkv, D], read in place" if args.fused_qkv
                         else "three packed arrays",
             "kernel_events": "every launch" if args.prefill_chunk or args.event_every <= 1

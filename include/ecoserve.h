@@ -264,7 +264,9 @@ int ecoserve_attn_decode_strided(ecoserve_ctx* ctx, const void* q, int64_t q_row
  * of one token per sequence at position ctx_len[b] - 1 followed by
  * ecoserve_attn_decode_strided, in one launch less: the wavefront that
  * streams a sequence's last cache block takes the new token's K and V from
- * the new rows and stores them into the block.
+ * the new rows, and the small launch that merges the split contexts also
+ * stores them into the block.  The cache holds the new tokens when the
+ * call's work on `stream` is complete, like every other result.
  *
  *   k_new, v_new     : dev, row b = the new token of sequence b, [Hkv][D], rows
  *                      new_row_stride elements apart (rules of the strided calls)

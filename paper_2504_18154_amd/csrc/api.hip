@@ -439,7 +439,7 @@ static int decode_impl(ecoserve_ctx* c, const void* q, int64_t q_row_stride, con
                              c->ws_splits, share_in, share_out, speed, wave_samples, cuts, two_per_cu, s);
     }
     if (e != hipSuccess) return ECOSERVE_EHIP;
-    e = launch_decode_mfma_merge(a, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, speed, wave_samples, cuts,
+    e = launch_decode_mfma_merge(a, ctx_len, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, speed, wave_samples, cuts,
                                  n_wgs * 4, s);
     return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
   }

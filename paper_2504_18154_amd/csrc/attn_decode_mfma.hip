@@ -367,12 +367,10 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
       auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // > 16 except in the sequence's last block
       // Fused append (k_new given): the sequence's newest token, slot t of its last block, is not in the
       // cache yet.  The wavefront that streams that block (exactly one per K/V head) takes the token's K
-      // and V from the new rows instead, in the operand layout the block's loads produce, and writes them
-      // to the slot, which nothing else in this launch reads.
-      auto append_token = [&](KVFrag& fr, int i, int t) {
-        const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, i) * blk_stride + head_off;
-        char* const kb = const_cast<char*>(k_cache) + off;
-        char* const vb = const_cast<char*>(v_cache) + off;
+      // and V from the new rows instead, in the operand layout the block's loads produce.  The slot itself
+      // is written by the merge launch that follows (stores here would sit in front of this wavefront's
+      // next wait for its loads).
+      auto append_token = [&](KVFrag& fr, int t) {
         // through LDS into the operand layout: lane l holds bytes [8 l, 8 l + 8) of (K row, V row)
         uint16_t* const st = s_new[wave];
         *reinterpret_cast<u32x2*>(st + lane * 4) = new_row;
@@ -384,7 +382,6 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
           for (int kk = 0; kk < 4; ++kk) {
             const bf16x8 x = *reinterpret_cast<const bf16x8*>(st + kk * 32 + quad * 8);
             fr.k[kk] = x;
-            *reinterpret_cast<bf16x8*>(kb + kk * 1024 + lane * 16) = x;
           }
         }
         if (quad == (t >> 2)) {
@@ -394,7 +391,6 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e)
               if (e == (t & 3)) fr.v[dt][e] = x;
-            *reinterpret_cast<short*>(vb + dt * 512 + col * 32 + quad * 8 + (t & 3) * 2) = x;
           }
         }
       };
@@ -410,7 +406,7 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
             const int tail = tail_of(i + d);
             if (k_new != nullptr && tail <= 16) {
               asm volatile("" ::: "memory");  // (a real branch: once per (sequence, head))
-              append_token(f[d], i + d, tail - 1);
+              append_token(f[d], tail - 1);
             }
             process_block(f[d], qf, acc, m, l, tail, quad, scale_log2e);
             done = i + d + 1 >= n;
@@ -490,6 +486,32 @@ __device__ __forceinline__ void measure_xcd_speed(float* __restrict__ xcd_speed,
   if (threadIdx.x == 0) xcd_speed[x] = n > idle ? v / n : 0.f;
 }
 
+// The fused append's stores, carried by the merge launch: token b of the new rows goes to position
+// ctx_len[b] - 1 of sequence b.  k_new == NULL: nothing to do.
+struct AppendJob {
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  int new_row_stride;
+  uint16_t* k_cache;
+  uint16_t* v_cache;
+  const int32_t* block_table;
+  int bt_stride;
+  const int32_t* ctx_len;
+  int B, Hkv;
+};
+// Workgroup `bid` of `n_blocks` (64 threads each) takes the (sequence, K/V head) pairs bid, bid + n_blocks, ...
+__device__ __forceinline__ void append_new_tokens(const AppendJob& j, int bid, int n_blocks) {
+  if (j.k_new == nullptr) return;
+  for (int pair = bid; pair < j.B * j.Hkv; pair += n_blocks) {
+    const int b = pair / j.Hkv, g = pair % j.Hkv;
+    const int p = j.ctx_len[b] - 1;
+    const int64_t blk = j.block_table[(size_t)b * j.bt_stride + (p >> 4)];
+    const size_t row = (size_t)b * j.new_row_stride + (size_t)g * 128;
+    append_one_row<uint16_t>(j.k_cache, j.v_cache, j.k_new + row, j.v_new + row, blk, g, p & 15, j.Hkv, 128,
+                             (int)threadIdx.x);
+  }
+}
+
 // The n_split partial states of one (sequence, query head), slots base .. base + n_split - 1, into its
 // output row (and log-sum-exp); one wavefront, lanes own pairs of head-vector elements.
 __device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
@@ -521,8 +543,9 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
                                                               uint16_t* __restrict__ out, float* __restrict__ lse,
                                                               float* __restrict__ xcd_speed,
                                                               const int32_t* __restrict__ ws_wave, int n_waves,
-                                                              int Hq, int Hkv, int G) {
+                                                              int Hq, int Hkv, int G, AppendJob job) {
   const int h = blockIdx.x, b = blockIdx.y, g = h / G;
+  append_new_tokens(job, b * Hq + h, (int)(gridDim.x * gridDim.y));
   if (xcd_speed && b * Hq + h < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, b * Hq + h);
   const Chunking ch = {ws_meta, ws_meta + 8};
   constexpr int kPieceCost = kPieceCostStream;  // (a forced split runs the one-per-SIMD shape)
@@ -544,12 +567,13 @@ __global__ __launch_bounds__(64) void decode_cut_merge_kernel(const float* __res
                                                              uint16_t* __restrict__ out, float* __restrict__ lse,
                                                              float* __restrict__ xcd_speed,
                                                              const int32_t* __restrict__ ws_wave, int n_waves,
-                                                             int Hq, int G) {
+                                                             int Hq, int G, AppendJob job) {
   const int w = blockIdx.x;
-  if (xcd_speed && w * G + (int)blockIdx.y < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, w * G + blockIdx.y);
-  const int n_split = ws_cut[4 * w];
-  if (n_split <= 1) return;
+  const int n_split = ws_cut[4 * w];  // (asked for before the append's own chain of loads, answered alongside it)
   const int b = ws_cut[4 * w + 1], h = ws_cut[4 * w + 2] * G + blockIdx.y;
+  append_new_tokens(job, w * G + (int)blockIdx.y, (int)(gridDim.x * gridDim.y));
+  if (xcd_speed && w * G + (int)blockIdx.y < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, w * G + blockIdx.y);
+  if (n_split <= 1) return;
   merge_partials(ws_acc, ws_ml, ((size_t)b * Hq + h) * ws_splits, n_split, out + ((size_t)b * Hq + h) * 128,
                  lse ? lse + (size_t)b * Hq + h : nullptr);
 }
@@ -585,18 +609,21 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   return hipGetLastError();
 }
 
-hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
+hipError_t launch_decode_mfma_merge(const AttnArgs& a, const int32_t* ctx_len, const float* ws_acc, const float* ws_ml,
                                     const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
                                     const int32_t* ws_wave, const int32_t* ws_cut, int32_t n_waves, hipStream_t s) {
+  const AppendJob job = {(const uint16_t*)a.k_new, (const uint16_t*)a.v_new, a.new_row_stride,
+                         (uint16_t*)const_cast<void*>(a.k_cache), (uint16_t*)const_cast<void*>(a.v_cache),
+                         a.block_table, a.bt_stride, ctx_len, a.B, a.Hkv};
   if (ws_cut) {
     hipLaunchKernelGGL(decode_cut_merge_kernel, dim3((unsigned)n_waves, (unsigned)(a.Hq / a.Hkv)), dim3(64), 0, s,
                        ws_acc, ws_ml, ws_cut, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq,
-                       a.Hq / a.Hkv);
+                       a.Hq / a.Hkv, job);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(decode_flat_merge_kernel, dim3((unsigned)a.Hq, (unsigned)a.B), dim3(64), 0, s, ws_acc, ws_ml,
                      ws_meta, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq, a.Hkv,
-                     a.Hq / a.Hkv);
+                     a.Hq / a.Hkv, job);
   return hipGetLastError();
 }
 

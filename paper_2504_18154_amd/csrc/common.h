@@ -152,7 +152,9 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
                               const float* share_in, float* share_out, const float* xcd_speed, int32_t* ws_wave,
                               int32_t* ws_cut, bool two_per_cu, hipStream_t s);
-hipError_t launch_decode_mfma_merge(const AttnArgs& a, const float* ws_acc, const float* ws_ml,
+// (with a.k_new given, the merge launch also stores every sequence's new token into the cache, position
+// ctx_len[b] - 1: the decode kernel has taken it from the new rows and left the cache alone)
+hipError_t launch_decode_mfma_merge(const AttnArgs& a, const int32_t* ctx_len, const float* ws_acc, const float* ws_ml,
                                     const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
                                     const int32_t* ws_wave, const int32_t* ws_cut, int32_t n_waves, hipStream_t s);
 
@@ -213,6 +215,21 @@ __device__ __forceinline__ size_t k_index(int64_t blk, int g, int slot, int d, i
 }
 __device__ __forceinline__ size_t v_index(int64_t blk, int g, int slot, int d, int Hkv, int D) {
   return (((size_t)blk * Hkv + g) * D + d) * kBlockSize + slot;
+}
+
+// One wavefront stores one new token of one (sequence, K/V head) into its cache slot: the K row as
+// 16-byte units, the V row scattered into the slot's column.  `lane` 0..63.
+template <typename E>
+__device__ __forceinline__ void append_one_row(E* __restrict__ k_cache, E* __restrict__ v_cache,
+                                               const E* __restrict__ ksrc, const E* __restrict__ vsrc, int64_t blk,
+                                               int g, int slot, int Hkv, int D, int lane) {
+  constexpr int X = Elem<E>::X;
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  E* kdst = k_cache + ((size_t)blk * Hkv + g) * 16 * D + (size_t)slot * X;
+  for (int c = lane; c < D / X; c += 64)
+    *reinterpret_cast<u4*>(kdst + (size_t)c * 16 * X) = *reinterpret_cast<const u4*>(ksrc + c * X);
+  E* vdst = v_cache + ((size_t)blk * Hkv + g) * D * 16 + slot;
+  for (int d = lane; d < D; d += 64) vdst[(size_t)d * 16] = vsrc[d];
 }
 
 __device__ __forceinline__ float wave_max(float v) {

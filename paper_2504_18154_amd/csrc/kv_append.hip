@@ -169,23 +169,16 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_one_kernel(E* __rest
                                                                         const int32_t* __restrict__ block_table,
                                                                         int bt_stride, int B, int Hkv, int D,
                                                                         int pos_bias) {
-  constexpr int X = Elem<E>::X;
-  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
   const int pair = blockIdx.x * (kAppendThreads / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (pair >= B * Hkv) return;
   const int b = pair / Hkv, g = pair % Hkv;
   // cu_q == NULL: exactly one token per sequence, token b belongs to sequence b
   const int tok = cu_q ? cu_q[b] : b;
   if (cu_q && cu_q[b + 1] - tok <= 0) return;
-  const int p = ctx_before[b] + pos_bias, slot = p & 15;
+  const int p = ctx_before[b] + pos_bias;
   const int64_t blk = block_table[(size_t)b * bt_stride + (p >> 4)];
-  const E* ksrc = k_new + (size_t)tok * new_row_stride + g * D;
-  E* kdst = k_cache + ((size_t)blk * Hkv + g) * 16 * D + (size_t)slot * X;
-  for (int c = lane; c < D / X; c += 64)
-    *reinterpret_cast<u4*>(kdst + (size_t)c * 16 * X) = *reinterpret_cast<const u4*>(ksrc + c * X);
-  const E* vsrc = v_new + (size_t)tok * new_row_stride + g * D;
-  E* vdst = v_cache + ((size_t)blk * Hkv + g) * D * 16 + slot;
-  for (int d = lane; d < D; d += 64) vdst[(size_t)d * 16] = vsrc[d];
+  append_one_row<E>(k_cache, v_cache, k_new + (size_t)tok * new_row_stride + g * D,
+                    v_new + (size_t)tok * new_row_stride + g * D, blk, g, p & 15, Hkv, D, lane);
 }
 
 // Dynamic LDS of the tiled kernel: the batch tables, then HPW staged V tiles.

@@ -285,7 +285,7 @@ def test_bf16_decode_of_hundreds_of_short_sequences():
     layer.close()
 
 
-@pytest.mark.parametrize("shape", ["bf16-G5", "bf16-mha", "bf16-many-short", "f32-plain"])
+@pytest.mark.parametrize("shape", ["bf16-G5", "bf16-mha", "bf16-many-short", "bf16-forced-split", "f32-plain"])
 def test_decode_with_the_append_fused_in(shape):
     """ecoserve_attn_decode_append against the two separate calls on a copy of the same cache: cache and
     output must agree bit for bit, step after step (positions crossing block boundaries, contexts that end
@@ -297,12 +297,16 @@ def test_decode_with_the_append_fused_in(shape):
         model, lens = wl.ModelShape("mha", 6, 6, 128, 1, "bf16"), [0, 15, 16, 31, 32, 700]
     elif shape == "bf16-many-short":
         model, lens = M30, list(np.random.default_rng(49).integers(0, 200, size=400))
+    elif shape == "bf16-forced-split":      # fixed chunks of 256 tokens: the other merge kernel carries the stores
+        model, lens = M30, [0, 1, 15, 16, 255, 256, 600, 2047]
     else:
         model, lens = M30, [0, 1, 14, 15, 16, 17, 255, 256, 1000, 2047, 3000]
     steps = 3
     say(f"fused append + decode, {shape}: {len(lens)} sequences, {steps} steps")
     lens = np.asarray(lens, dtype=np.int32)
     pb, layer = _mk(model, lens + steps, seed=62)
+    if shape == "bf16-forced-split":
+        layer.ctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, 256)
     table = dev_i32(pb.block_table)
     if lens.sum() > 0:
         _, k, v = _qkv(model, int(lens.sum()), 620)
