@@ -48,8 +48,9 @@ constexpr int kWaves = 4;
 // budget; a second wavefront per SIMD buys nothing there (the memory pipeline serves the older one
 // first).  <3, 2> is for batches cut into many short pieces (hundreds of short sequences): a piece ends
 // with the pipeline drained and a few stores, and only another wavefront on the SIMD can fill that gap
-// (measured: 1024 sequences of ~100 tokens 171 -> 145 us, 512 of ~400 tokens 208 -> 195 us; the
-// benchmark's 128 sequences of 512..4096 tokens 228 -> 229 us).
+// (measured with plain loads: 1024 sequences of ~100 tokens 171 -> 145 us, 512 of ~400 tokens 208 -> 195 us,
+// the benchmark's 128 sequences of 512..4096 tokens 228 -> 229 us; with the non-temporal loads below the
+// edge has shrunk to 114 -> 113 us on the first, and the second is better off in the streaming shape).
 
 struct KVFrag {
   bf16x8 k[4];   // K block: unit (4*kk + quad, token = col)  ->  A operand of S^T step kk

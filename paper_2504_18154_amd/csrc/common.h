@@ -16,7 +16,7 @@ constexpr int kMinSplitTokens = 64;   // smallest decode split
 constexpr int kMaxSplitTokens = 4096; // largest forced decode split
 constexpr int kDecodeWgsPerCu = 1;    // persistent decode grid: workgroups per CU (one wavefront per SIMD) ...
 constexpr int kDecodeMaxWgsPerCu = 2; // ... two for a batch of many short (sequence, head) pieces
-constexpr int kDecodeManyPieces = 3;  // that is: this many (sequence, K/V head)s per wavefront of the one-per-CU grid
+constexpr int kDecodeManyPieces = 6;  // that is: this many (sequence, K/V head)s per wavefront of the one-per-CU grid
 constexpr int kMaxBatch = 4096;       // largest max_batch a context accepts (batch prefix sums live in LDS)
 constexpr int kPrefillTileRows = 128; // query rows of one prefill work item
 constexpr int kPrefillWgsPerCu = 2;   // persistent prefill grid: workgroups per CU

@@ -258,15 +258,15 @@ def test_append_at_the_largest_batch(dtype):
 
 
 def test_bf16_decode_of_hundreds_of_short_sequences():
-    """420 sequences of 1..300 tokens with 8 K/V heads: more than three (sequence, head) pieces per
+    """800 sequences of 1..150 tokens with 8 K/V heads: more than six (sequence, head) pieces per
     wavefront of the one-workgroup-per-CU grid, so the library launches its two-workgroups-per-CU shape,
     and nearly every (sequence, head) is written in final form by the decode kernel while the merge
     handles the few that a chunk boundary cuts.  Equal and measured per-XCD shares."""
     from paper_2504_18154_amd import binding
     model = M30
     rng = np.random.default_rng(47)
-    lens = rng.integers(1, 301, size=420)
-    lens[[0, 1, 419]] = [1, 300, 16]
+    lens = rng.integers(1, 151, size=800)
+    lens[[0, 1, 799]] = [1, 300, 16]
     say(f"bf16 decode of {len(lens)} short sequences, {int(lens.sum())} tokens")
     pb, layer = _mk(model, lens, seed=48)
     _, k, v = _qkv(model, pb.T, 470)
@@ -296,7 +296,7 @@ def test_decode_with_the_append_fused_in(shape):
     elif shape == "bf16-mha":
         model, lens = wl.ModelShape("mha", 6, 6, 128, 1, "bf16"), [0, 15, 16, 31, 32, 700]
     elif shape == "bf16-many-short":
-        model, lens = M30, list(np.random.default_rng(49).integers(0, 200, size=400))
+        model, lens = M30, list(np.random.default_rng(49).integers(0, 100, size=800))   # two workgroups per CU
     elif shape == "bf16-forced-split":      # fixed chunks of 256 tokens: the other merge kernel carries the stores
         model, lens = M30, [0, 1, 15, 16, 255, 256, 600, 2047]
     else:
