@@ -506,6 +506,7 @@ __device__ __forceinline__ void append_new_tokens(const AppendJob& j, int bid, i
   for (int pair = bid; pair < j.B * j.Hkv; pair += n_blocks) {
     const int b = pair / j.Hkv, g = pair % j.Hkv;
     const int p = j.ctx_len[b] - 1;
+    if (p < 0) continue;  // an empty sequence has no new token (and no output row worth reading)
     const int64_t blk = j.block_table[(size_t)b * j.bt_stride + (p >> 4)];
     const size_t row = (size_t)b * j.new_row_stride + (size_t)g * 128;
     append_one_row<uint16_t>(j.k_cache, j.v_cache, j.k_new + row, j.v_new + row, blk, g, p & 15, j.Hkv, 128,

@@ -176,6 +176,7 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_one_kernel(E* __rest
   const int tok = cu_q ? cu_q[b] : b;
   if (cu_q && cu_q[b + 1] - tok <= 0) return;
   const int p = ctx_before[b] + pos_bias;
+  if (p < 0) return;  // (pos_bias -1 on an empty sequence: nothing to store)
   const int64_t blk = block_table[(size_t)b * bt_stride + (p >> 4)];
   append_one_row<E>(k_cache, v_cache, k_new + (size_t)tok * new_row_stride + g * D,
                     v_new + (size_t)tok * new_row_stride + g * D, blk, g, p & 15, Hkv, D, lane);

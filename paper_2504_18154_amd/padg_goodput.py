@@ -13,8 +13,9 @@ Profile, measured on the GPU at hand (step 1):
     plus the layer's dense projections (Eq. 1, Eq. 3) as library GEMMs through torch.matmul on random weights
     (hidden = Hq * D, intermediate 27648: a 31 B-parameter model with the benchmark's head shape), times the
     number of layers;
-  * one decode step over b sequences with t cached tokens, over a grid of (b, t): per layer kv_append (one
-    token each) + attn_decode + the same projections for b tokens, times the layers; a least-squares fit
+  * one decode step over b sequences with t cached tokens, over a grid of (b, t): per layer
+    attn_decode_append (one new token each, appended and attended to) + the same projections for b tokens,
+    times the layers; a least-squares fit
     gives base + per-sequence + per-token costs.
 Simulation (step 2, host only): Poisson arrivals, lengths from workloads.table4_lengths, a sweep over request
 rates; prints one JSON line per dataset with the attainment curve and the goodput at 90%.
@@ -108,13 +109,11 @@ def measure_profile(model, layers: int):
         x = wl.randn((b, H), "bf16", 2, device=dev)
         out = torch.empty((b, model.Hq, model.D), dtype=torch.bfloat16, device=dev)
         bt, cl = i32(db.block_table), i32(db.ctx_len)
-        cu, before = i32(np.arange(b + 1)), i32(db.ctx_len - 1)
 
         def layer():
             qkv = dense(x)
             q, k, v = qkv[:, :model.Hq], qkv[:, model.Hq:model.Hq + model.Hkv], qkv[:, model.Hq + model.Hkv:]
-            ctx.kv_append_strided(kc, vc, k, v, cu, before, bt, max_new_len=1)
-            ctx.attn_decode_strided(q, kc, vc, bt, cl, out, db.max_ctx_len)
+            ctx.attn_decode_append(q, k, v, kc, vc, bt, cl, out, db.max_ctx_len)
             dense_tail(out)
 
         us = timed(layer, 50) * layers
