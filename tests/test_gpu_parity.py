@@ -691,7 +691,7 @@ def test_fused_projection_rows_are_read_in_place(dtype, pad):
 
 
 def test_hot_calls_can_be_captured_in_a_hip_graph():
-    """One decode step of three layers (append one token, decode) and one prefill call recorded into a HIP
+    """One decode step of three layers (append one token, decode; one of them as the fused call) and one prefill call recorded into a HIP
     graph and replayed three times with new input contents and the program's own eager work in between:
     every replay must give exactly what the eager calls give on the same inputs.  The hot calls neither
     allocate nor synchronise, so a capturing stream can take them (default options: equal decode shares, a
@@ -719,6 +719,9 @@ def test_hot_calls_can_be_captured_in_a_hip_graph():
 
     def work():
         for i, L in enumerate(Ls):
+            if i == 1:          # the middle layer through the fused call
+                L.ctx.attn_decode_append(q, kn, vn, L.kc, L.vc, table, ctx, out[i], max(lens) + 1)
+                continue
             L.ctx.kv_append(L.kc, L.vc, kn, vn, ones, before, table, max_new_len=1)
             L.ctx.attn_decode(q, L.kc, L.vc, table, ctx, out[i], max(lens) + 1)
         Ls[0].ctx.attn_prefill(qp, Ls[0].kc, Ls[0].vc, cu, zero, table, outp, max_q_len=max(lens))
