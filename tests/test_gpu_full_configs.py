@@ -9,7 +9,7 @@ import torch
 
 from oracle import oracle as orc
 from paper_2504_18154_amd import binding, workloads as wl
-from tests.parity_util import Layer, compare, compare_lse, say
+from tests.parity_util import Layer, compare, compare_lse, dev_i32, say
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +55,23 @@ def _decode_full(db: wl.DecodeBatch, name):
         out, lse = layer.decode_gpu(q, db.block_table, db.ctx_len)
         compare(f"{name} decode, adaptive shares, call {call}", out, ref, "bf16")
         compare_lse(f"{name} decode, adaptive shares, call {call}", lse, ref_lse, "bf16")
+    # ... and the call bench.py times: the step's append fused into the decode call.  The last token of
+    # every sequence is wiped from the cache (NaN bits) and handed in as the step's new token: the output
+    # must still match the oracle and the cache must be whole again afterwards.
+    cu = wl.cu_from_lengths(db.ctx_len)
+    last = torch.as_tensor(cu[1:] - 1, dtype=torch.int64, device="cuda")
+    kn, vn = k[last].contiguous(), v[last].contiguous()
+    wipe = torch.full_like(kn, float("nan"))
+    table, ctx_dev = dev_i32(db.block_table), dev_i32(db.ctx_len)
+    layer.ctx.kv_append(layer.kc, layer.vc, wipe, wipe, dev_i32(wl.cu_from_lengths([1] * db.B)),
+                        dev_i32(db.ctx_len - 1), table, max_new_len=1)
+    for call in range(2):
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full((db.B, model.Hq), float("nan"), dtype=torch.float32, device="cuda")
+        layer.ctx.attn_decode_append(q, kn, vn, layer.kc, layer.vc, table, ctx_dev, out, db.max_ctx_len, lse)
+        compare(f"{name} fused append + decode, call {call}", out, ref, "bf16")
+        compare_lse(f"{name} fused append + decode, call {call}", lse, ref_lse, "bf16")
+        layer.assert_cache_bit_exact()
     layer.close()
 
 
