@@ -23,8 +23,9 @@
 // the next launch.
 //
 // Per piece, the wavefront streams whole cache blocks with fully coalesced per-lane loads
-// that land directly in MFMA operand layout - no LDS staging, no barriers, a register
-// pipeline kDepth blocks deep, physical block ids prefetched 64 at a time into one VGPR:
+// (non-temporal buffer loads through a descriptor per block, see load_block) that land
+// directly in MFMA operand layout - no LDS staging, no barriers, a register pipeline
+// kDepth blocks deep, physical block ids prefetched 64 at a time into one VGPR:
 //   scores  S^T[token][head] = K . Q^T   v_mfma_f32_16x16x32_bf16 (heads padded to 16 columns)
 //   online softmax per column in the exp2 domain; the four 16-lane groups hold different
 //   tokens of the same head, their maxima are combined with wavefront shuffles
@@ -32,7 +33,9 @@
 // The accumulator layout of the first product is already the B-operand layout of the
 // second, so P never leaves registers.  A piece that is a whole (sequence, head) writes the
 // final output; otherwise (m, l, unnormalised o) go to the workspace and a small merge
-// kernel combines them exactly.
+// kernel combines them exactly.  With the step's append fused in (k_new given), the wavefront
+// that reaches a sequence's last block takes the new token from the new rows, and the merge
+// launch stores it into the cache.
 //
 // Lane layouts relied upon (lane = 16*quad + col):
 //   16x16x32:  A[row=col][k = 8*quad .. 8*quad+7],  B[k = 8*quad..+7][col],
