@@ -46,10 +46,11 @@
 namespace eco {
 
 constexpr int kWaves = 4;
-// The kernel comes in two shapes (template arguments: cache blocks of 8 KiB in flight per wavefront,
-// workgroups per CU).  <4, 1> is the streaming shape: one wavefront per SIMD with the whole register
-// budget; a second wavefront per SIMD buys nothing there (the memory pipeline serves the older one
-// first).  <3, 2> is for batches cut into many short pieces (hundreds of short sequences): a piece ends
+// The kernel comes in two shapes (template arguments: cache blocks of 8 KiB in flight per wavefront plus
+// one, workgroups per CU).  <3, 1> is the streaming shape: one wavefront per SIMD; a second wavefront per
+// SIMD buys nothing there (the memory pipeline serves the older one first), and a fourth block in flight
+// needs more registers than the pipeline's state leaves (the compiler then parks fragments in AGPRs and
+// copies them back: 3% slower on long contexts).  <3, 2> is for batches cut into many short pieces (hundreds of short sequences): a piece ends
 // with the pipeline drained and a few stores, and only another wavefront on the SIMD can fill that gap
 // (measured with plain loads: 1024 sequences of ~100 tokens 171 -> 145 us, 512 of ~400 tokens 208 -> 195 us,
 // the benchmark's 128 sequences of 512..4096 tokens 228 -> 229 us; with the non-temporal loads below the
@@ -127,13 +128,15 @@ __device__ __forceinline__ void process_block(KVFrag& f, const bf16x8 (&qf)[4], 
   for (int dt = 0; dt < 8; ++dt) acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(f.v[dt], pbits, acc[dt], 0, 0, 0);
 }
 
-// A piece costs a wavefront several blocks' worth of time (its pipeline fill and drain, its result's
-// stores: a wavefront's end time rises by ~3 us with every piece in its chunk), and some chunks hold a
-// dozen pieces when others hold one.  So that equal chunks are equal work, every (sequence, K/V head) is
-// numbered with kPieceCost units in front of its blocks that stand for that cost and hold no data (in
-// units of a block's time, which differs between the kernel's two shapes).
-// (values from a sweep over 0..12 on five batch shapes: flat between 6 and 8 / 4 and 6, worse outside)
-constexpr int kPieceCostStream = 6;  // one wavefront per SIMD
+// A piece costs a wavefront several blocks' worth of time (finding it, its query rows, its result; before
+// the block pipeline ran through from piece to piece also a fill and a drain: a wavefront's end time rose
+// by ~3 us with every piece in its chunk), and some chunks hold a dozen pieces when others hold one.  So
+// that equal chunks are equal work, every (sequence, K/V head) is numbered with kPieceCost units in front
+// of its blocks that stand for that cost and hold no data (in units of a block's time).
+// (values from sweeps on five batch shapes: 2, 3, 4, 6 for the first - 512 sequences of ~400 tokens take
+// 159.6, 154.7, 154.1, 157.0 us - and 2, 3, 4 for the second - 1024 sequences of ~100 tokens 111.5, 109.0,
+// 108.1 us; the benchmark batches do not care)
+constexpr int kPieceCostStream = 4;  // one wavefront per SIMD
 constexpr int kPieceCostShared = 4;  // two per SIMD: a block takes about twice as much of a wavefront's time
 
 // Exclusive prefix sums of the per-sequence unit counts (blocks + kPieceCost) into LDS: pre[b] = units
@@ -215,6 +218,8 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
   __shared__ int wsum[kWaves];
   __shared__ int s_c[8], s_cum[9];
   __shared__ __attribute__((aligned(16))) uint16_t s_new[kWaves][256];  // fused append: a token's K row, then its V row
+  constexpr int kOutBytes = kWgsPerCu == 2 ? 8192 : 16384;
+  __shared__ __attribute__((aligned(16))) char s_out[kWaves][kOutBytes];  // final results on their way out
   const long long t_start = wall_clock64();
   constexpr int kPieceCost = kWgsPerCu == 2 ? kPieceCostShared : kPieceCostStream;
   scan_block_counts(pre, lens, wsum, ctx_len, B, kPieceCost);
@@ -323,135 +328,209 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
     return id;
   };
 
+  // Final results wait in LDS and go out together (when the wavefront's buffer is full, and at the end of
+  // its chunk): a global store in the middle of the stream would make the next wait for a K/V load a full
+  // drain (loads and stores pending together count as unordered), and the block pipeline below runs through
+  // piece after piece without one.  An entry: G output rows of 256 bytes (contiguous in `out` too), G
+  // log-sum-exps, (sequence, K/V head).
+  const int entry_bytes = G * 256 + 64 + 16;
+  const int k_entries = kOutBytes / entry_bytes;  // >= 1: G <= 16
+  char* const obuf = s_out[wave];
+  int n_buf = 0;
+  auto flush = [&]() {
+    for (int e = 0; e < n_buf; ++e) {
+      const char* ent = obuf + e * entry_bytes;
+      const int eb = *reinterpret_cast<const int*>(ent + G * 256 + 64);
+      const int eg = *reinterpret_cast<const int*>(ent + G * 256 + 68);
+      char* orow = reinterpret_cast<char*>(out + ((size_t)eb * Hq + (size_t)eg * G) * 128);
+      for (int idx = lane; idx < G * 16; idx += 64)
+        *reinterpret_cast<u32x4*>(orow + idx * 16) = *reinterpret_cast<const u32x4*>(ent + idx * 16);
+      if (lse && lane < G) lse[(size_t)eb * Hq + eg * G + lane] = *reinterpret_cast<const float*>(ent + G * 256 + lane * 4);
+    }
+    n_buf = 0;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing but loads pending from here on
+  };
+
   long long u = u_begin;
   Piece cur = locate(u);
-  bf16x8 qf[4];
-  load_q(qf, cur);
-  int ids = load_ids(cur, 0);
-  for (;;) {
-    if (cur.n == 0) break;  // only the cost units of the next (sequence, head) are left in this chunk
-    const long long u_next = cur.u_stop;
-    const bool has_next = u_next < u_end;
-    Piece nxt = cur;
-    bf16x8 qn[4];
-    int ids_n = 0;
-    if (has_next) {
-      nxt = locate(u_next);
-      load_q(qn, nxt);
-      ids_n = load_ids(nxt, 0);
-    }
-    const size_t head_off = (size_t)cur.g * 4096;
-    const int L = cur.L;
-    // fused append: if this piece reaches the end of its sequence, the new token's K and V rows (512 bytes)
-    // are fetched now, 8 bytes per lane, and wait in two registers until the last block is worked on
-    u32x2 new_row = {0u, 0u};
-    if (k_new != nullptr && cur.blk0 + cur.n == cur.nb) {
-      const size_t row = (size_t)cur.b * new_row_stride + (size_t)cur.g * 128 + (lane & 31) * 4;
-      new_row = *reinterpret_cast<const u32x2*>((lane < 32 ? k_new : v_new) + row);
-    }
-
-    f32x4 acc[8];
+  if (cur.n > 0) {  // (else: only the cost units of a (sequence, head) fall into this chunk)
+    bf16x8 qf[4];
+    load_q(qf, cur);
+    int ids = load_ids(cur, 0);
+    const size_t blk_stride_ = blk_stride;
+    // Register pipeline kDepth blocks deep, running without a break through the whole chunk.  Blocks are
+    // taken in windows of up to 64 (the ids one VGPR holds); a window of n blocks occupies np = n rounded
+    // up to kDepth pipeline slots (the slots behind its last block do no work and their loads are loads of
+    // nothing), so every window starts on f[0] and the loop has one shape.  Slot t's load is issued
+    // kDepth - 1 slots early; the issue slots that reach past a window fetch the first blocks of what
+    // follows it (the piece's next 64 blocks, or the next piece), which therefore arrive while this
+    // window's last blocks are worked on: a change of window or piece does not drain the pipeline.  Every
+    // slot issues the same twelve loads, so the number in flight never varies and waits stay precise.
+    KVFrag f[kDepth];
+    {
+      const int n0 = min(64, cur.n);
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;
+      for (int d = 0; d < kDepth - 1; ++d) {
+        const size_t off = (size_t)__builtin_amdgcn_readlane(ids, min(d, n0 - 1)) * blk_stride_ + (size_t)cur.g * 4096;
+        load_block(f[d], k_cache + off, v_cache + off, d < n0, lane, col, quad);
+      }
+    }
+    for (;;) {
+      const long long u_next = cur.u_stop;
+      const bool has_next = u_next < u_end;
+      Piece nxt = cur;
+      bf16x8 qn[4];
+      int ids_n = 0;
+      if (has_next) {
+        nxt = locate(u_next);
+        load_q(qn, nxt);
+        ids_n = load_ids(nxt, 0);
+      }
+      const size_t head_off = (size_t)cur.g * 4096;
+      const int L = cur.L;
+      // fused append: if this piece reaches the end of its sequence, the new token's K and V rows (512 bytes)
+      // are fetched now, 8 bytes per lane, and wait in two registers until the last block is worked on
+      u32x2 new_row = {0u, 0u};
+      if (k_new != nullptr && cur.blk0 + cur.n == cur.nb) {
+        const size_t row = (size_t)cur.b * new_row_stride + (size_t)cur.g * 128 + (lane & 31) * 4;
+        new_row = *reinterpret_cast<const u32x2*>((lane < 32 ? k_new : v_new) + row);
+      }
 
-    for (int base = 0; base < cur.n; base += 64) {
-      const int n = min(64, cur.n - base);
-      const int my_id = ids;
-      if (base + 64 < cur.n) ids = load_ids(cur, base + 64);  // ids of the following 64 blocks, early
-      // Register pipeline kDepth blocks deep.  Loads are issued unconditionally, those past the
-      // end of the piece as loads of nothing (index clamped to the last block, zero-byte
-      // descriptor), so the number of loads in flight is the same on every path and waits
-      // stay precise.
-      auto issue = [&](KVFrag& f, int i) {
-        const int ii = min(i, n - 1);
-        const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, ii) * blk_stride + head_off;
-        load_block(f, k_cache + off, v_cache + off, i < n, lane, col, quad);
-      };
-      auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // > 16 except in the sequence's last block
-      // Fused append (k_new given): the sequence's newest token, slot t of its last block, is not in the
-      // cache yet.  The wavefront that streams that block (exactly one per K/V head) takes the token's K
-      // and V from the new rows instead, in the operand layout the block's loads produce.  The slot itself
-      // is written by the merge launch that follows (stores here would sit in front of this wavefront's
-      // next wait for its loads).
-      auto append_token = [&](KVFrag& fr, int t) {
-        // through LDS into the operand layout: lane l holds bytes [8 l, 8 l + 8) of (K row, V row)
-        uint16_t* const st = s_new[wave];
-        *reinterpret_cast<u32x2*>(st + lane * 4) = new_row;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (col == t) {
+      f32x4 acc[8];
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 x = *reinterpret_cast<const bf16x8*>(st + kk * 32 + quad * 8);
-            fr.k[kk] = x;
+      for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      float m = -INFINITY, l = 0.f;
+
+      int base = 0;
+      do {  // (bottom-tested loops: the compiler then knows that loads were issued since the piece began)
+        const int n = min(64, cur.n - base);
+        const int my_id = ids;
+        const bool more = base + 64 < cur.n;
+        if (more) ids = load_ids(cur, base + 64);  // ids of the following 64 blocks, early
+        // what follows this window: the piece's next 64 blocks, or the first blocks of the next piece
+        const size_t nhead = more ? head_off : (size_t)nxt.g * 4096;
+        const int nn = more ? min(64, cur.n - base - 64) : (has_next ? min(64, nxt.n) : 0);
+        const int np = (n + kDepth - 1) / kDepth * kDepth;
+        auto issue = [&](KVFrag& fr, int t, bool may_follow) {  // the load of pipeline slot t (t < np + kDepth - 1)
+          size_t off;
+          bool live = t < n;
+          if (may_follow && t >= np && t - np < nn) {
+            // (kept a real branch: taken only behind a window's end, and reading the ids earlier would
+            // wait for a load that has only just been issued)
+            asm volatile("" ::: "memory");
+            int id;
+            if (more) {
+              id = __builtin_amdgcn_readlane(ids, t - np);
+            } else {
+              asm volatile("" ::: "memory");
+              id = __builtin_amdgcn_readlane(ids_n, t - np);
+            }
+            off = (size_t)id * blk_stride_ + nhead;
+            live = true;
+          } else {
+            off = (size_t)__builtin_amdgcn_readlane(my_id, min(t, n - 1)) * blk_stride_ + head_off;
+          }
+          load_block(fr, k_cache + off, v_cache + off, live, lane, col, quad);
+        };
+        auto tail_of = [&](int i) { return L - ((cur.blk0 + base + i) << 4); };  // > 16 except in the sequence's last block
+        // Fused append (k_new given): the sequence's newest token, slot t of its last block, is not in the
+        // cache yet.  The wavefront that streams that block (exactly one per K/V head) takes the token's K
+        // and V from the new rows instead, in the operand layout the block's loads produce.  The slot itself
+        // is written by the merge launch that follows.
+        auto append_token = [&](KVFrag& fr, int t) {
+          // through LDS into the operand layout: lane l holds bytes [8 l, 8 l + 8) of (K row, V row)
+          uint16_t* const st = s_new[wave];
+          *reinterpret_cast<u32x2*>(st + lane * 4) = new_row;
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          if (col == t) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) fr.k[kk] = *reinterpret_cast<const bf16x8*>(st + kk * 32 + quad * 8);
+          }
+          if (quad == (t >> 2)) {
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+              const short x = (short)st[128 + dt * 16 + col];
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (e == (t & 3)) fr.v[dt][e] = x;
+            }
+          }
+        };
+        int i = 0;
+        // the body of a window: every slot it issues lies inside the window and no block is the sequence's last
+        for (; i + 2 * kDepth - 1 <= n; i += kDepth) {
+#pragma unroll
+          for (int d = 0; d < kDepth; ++d) {
+            const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, i + d + kDepth - 1) * blk_stride_ + head_off;
+            load_block(f[(d + kDepth - 1) % kDepth], k_cache + off, v_cache + off, true, lane, col, quad);
+            process_block(f[d], qf, acc, m, l, 16, quad, scale_log2e);
           }
         }
-        if (quad == (t >> 2)) {
+        // its last one or two rounds (at least kDepth - 1 blocks are left): the general form
+        do {
+#pragma unroll
+          for (int d = 0; d < kDepth; ++d) {
+            issue(f[(d + kDepth - 1) % kDepth], i + d + kDepth - 1, d > 0);  // (slot i + kDepth - 1 is never past the window)
+            if (i + d < n) {
+              const int tail = tail_of(i + d);
+              if (k_new != nullptr && tail <= 16) {
+                asm volatile("" ::: "memory");  // (a real branch: once per (sequence, head))
+                append_token(f[d], tail - 1);
+              }
+              process_block(f[d], qf, acc, m, l, tail, quad, scale_log2e);
+            }
+          }
+          i += kDepth;
+        } while (i < np);
+        base += 64;
+      } while (base < cur.n);
+
+      // ---- this piece's result: lanes (col = head, quad) hold o[d = 16 dt + 4 quad + i] --------
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      if (cur.n == cur.nb) {  // the whole (sequence, head): final, into the LDS buffer
+        if (n_buf == k_entries) flush();
+        char* ent = obuf + n_buf * entry_bytes;
+        if (col < G) {
+          const float inv = 1.f / l;
 #pragma unroll
           for (int dt = 0; dt < 8; ++dt) {
-            const short x = (short)st[128 + dt * 16 + col];
+            u32x2 w;
+            w[0] = (uint32_t)float_to_bf16_bits(acc[dt][0] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][1] * inv) << 16);
+            w[1] = (uint32_t)float_to_bf16_bits(acc[dt][2] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][3] * inv) << 16);
+            *reinterpret_cast<u32x2*>(ent + col * 256 + (dt * 16 + 4 * quad) * 2) = w;
+          }
+          if (quad == 0) *reinterpret_cast<float*>(ent + G * 256 + col * 4) = (m + log2f(l)) * kLn2;
+        }
+        if (lane == 0) {
+          *reinterpret_cast<int*>(ent + G * 256 + 64) = cur.b;
+          *reinterpret_cast<int*>(ent + G * 256 + 68) = cur.g;
+        }
+        ++n_buf;
+      } else {  // a cut (sequence, head): at most the first and the last piece of a chunk
+        if (col < G) {
+          const int h = cur.g * G + col;
+          const int split = gw - ch.owner(cur.seg_u0 + kPieceCost);  // counted from the chunk that holds block 0
+          const size_t slot = ((size_t)cur.b * Hq + h) * ws_splits + split;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (e == (t & 3)) fr.v[dt][e] = x;
+          for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
+          if (quad == 0) {
+            ws_ml[slot * 2 + 0] = m;
+            ws_ml[slot * 2 + 1] = l;
           }
         }
-      };
-      KVFrag f[kDepth];
-#pragma unroll
-      for (int d = 0; d < kDepth - 1; ++d) issue(f[d], d);
-      for (int i = 0; i < n; i += kDepth) {
-        bool done = false;
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-          if (!done) {
-            issue(f[(d + kDepth - 1) % kDepth], i + d + kDepth - 1);
-            const int tail = tail_of(i + d);
-            if (k_new != nullptr && tail <= 16) {
-              asm volatile("" ::: "memory");  // (a real branch: once per (sequence, head))
-              append_token(f[d], tail - 1);
-            }
-            process_block(f[d], qf, acc, m, l, tail, quad, scale_log2e);
-            done = i + d + 1 >= n;
-          }
-        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (see flush)
       }
+      if (!has_next || nxt.n == 0) break;  // n == 0: only the cost units of the next (sequence, head) are left
+      u = u_next;
+      cur = nxt;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) qf[kk] = qn[kk];
+      ids = ids_n;
     }
-
-    // ---- this piece's result: lanes (col = head, quad) hold o[d = 16 dt + 4 quad + i] --------
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    if (col < G) {
-      const int h = cur.g * G + col;
-      if (cur.n == cur.nb) {  // the whole (sequence, head): final
-        const float inv = 1.f / l;
-        uint16_t* orow = out + ((size_t)cur.b * Hq + h) * 128;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-          u32x2 w;
-          w[0] = (uint32_t)float_to_bf16_bits(acc[dt][0] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][1] * inv) << 16);
-          w[1] = (uint32_t)float_to_bf16_bits(acc[dt][2] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][3] * inv) << 16);
-          *reinterpret_cast<u32x2*>(orow + dt * 16 + 4 * quad) = w;
-        }
-        if (lse && quad == 0) lse[(size_t)cur.b * Hq + h] = (m + log2f(l)) * kLn2;
-      } else {
-        const int split = gw - ch.owner(cur.seg_u0 + kPieceCost);  // counted from the chunk that holds block 0
-        const size_t slot = ((size_t)cur.b * Hq + h) * ws_splits + split;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
-        if (quad == 0) {
-          ws_ml[slot * 2 + 0] = m;
-          ws_ml[slot * 2 + 1] = l;
-        }
-      }
-    }
-    if (!has_next) break;
-    u = u_next;
-    cur = nxt;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) qf[kk] = qn[kk];
-    ids = ids_n;
+    flush();
   }
   if (ws_cut && lane == 0) {
     // For the merge kernel: a (sequence, K/V head) that starts in this chunk and runs on into later ones
@@ -610,7 +689,7 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   if (two_per_cu)
     launch(decode_mfma_kernel<3, 2>);
   else
-    launch(decode_mfma_kernel<4, 1>);
+    launch(decode_mfma_kernel<3, 1>);
   return hipGetLastError();
 }
 
