@@ -194,7 +194,7 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   if (st != ECOSERVE_OK) { delete c; return st; }
   {
     // per-XCD shares start equal; samples of 4 wavefronts per CU follow, then each chunk's report to the merge
-    const size_t share_bytes = (24 + 6 * (size_t)c->num_cu * kDecodeMaxWgsPerCu * 4) * sizeof(int32_t);
+    const size_t share_bytes = (24 + 6 * (size_t)c->num_cu * kDecodeWgsPerCu * 4) * sizeof(int32_t);
     const float ones[16] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
     if (hipMalloc(&c->ws_share, share_bytes) != hipSuccess || hipMemset(c->ws_share, 0, share_bytes) != hipSuccess ||
         hipMemcpy(c->ws_share, ones, sizeof(ones), hipMemcpyHostToDevice) != hipSuccess) {
@@ -421,22 +421,19 @@ static int decode_impl(ecoserve_ctx* c, const void* q, int64_t q_row_stride, con
     a.k_new = k_new;
     a.v_new = v_new;
     a.new_row_stride = (int32_t)new_row_stride;
-    // many short pieces per wavefront (hundreds of short sequences): two workgroups per CU fill each other's gaps
-    const bool two_per_cu = c->opt_split_tokens == 0 &&
-                            (int64_t)B * c->lay.num_kv_heads >= (int64_t)kDecodeManyPieces * c->num_cu * kDecodeWgsPerCu * 4;
-    const int n_wgs = c->num_cu * (two_per_cu ? kDecodeMaxWgsPerCu : kDecodeWgsPerCu);
+    const int n_wgs = c->num_cu * kDecodeWgsPerCu;
     const bool adaptive = c->opt_adaptive && c->opt_split_tokens == 0 && n_wgs % 8 == 0;
     const float* const share_in = adaptive ? c->ws_share + 8 * c->share_parity : nullptr;
     float* const share_out = adaptive ? c->ws_share + 8 * (1 - c->share_parity) : nullptr;
     float* const speed = adaptive ? c->ws_share + 16 : nullptr;
     int32_t* const wave_samples = adaptive ? reinterpret_cast<int32_t*>(c->ws_share + 24) : nullptr;
     // the persistent grid lists its cut (sequence, head)s for the merge; a forced split has its own, larger grid
-    int32_t* const cuts = c->opt_split_tokens == 0 ? reinterpret_cast<int32_t*>(c->ws_share + 24) + 2 * c->num_cu * kDecodeMaxWgsPerCu * 4 : nullptr;
+    int32_t* const cuts = c->opt_split_tokens == 0 ? reinterpret_cast<int32_t*>(c->ws_share + 24) + 2 * c->num_cu * kDecodeWgsPerCu * 4 : nullptr;
     if (adaptive) c->share_parity ^= 1;
     {
       ProfileScope prof(c, ECOSERVE_KERNEL_DECODE, s);
       e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len, n_wgs, c->ws_acc, c->ws_ml, c->ws_meta,
-                             c->ws_splits, share_in, share_out, speed, wave_samples, cuts, two_per_cu, s);
+                             c->ws_splits, share_in, share_out, speed, wave_samples, cuts, s);
     }
     if (e != hipSuccess) return ECOSERVE_EHIP;
     e = launch_decode_mfma_merge(a, ctx_len, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, speed, wave_samples, cuts,

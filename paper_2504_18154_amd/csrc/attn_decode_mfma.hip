@@ -46,15 +46,13 @@
 namespace eco {
 
 constexpr int kWaves = 4;
-// The kernel comes in two shapes (template arguments: cache blocks of 8 KiB in flight per wavefront plus
-// one, workgroups per CU).  <3, 1> is the streaming shape: one wavefront per SIMD; a second wavefront per
-// SIMD buys nothing there (the memory pipeline serves the older one first), and a fourth block in flight
-// needs more registers than the pipeline's state leaves (the compiler then parks fragments in AGPRs and
-// copies them back: 3% slower on long contexts).  <3, 2> is for batches cut into many short pieces (hundreds of short sequences): a piece ends
-// with the pipeline drained and a few stores, and only another wavefront on the SIMD can fill that gap
-// (measured with plain loads: 1024 sequences of ~100 tokens 171 -> 145 us, 512 of ~400 tokens 208 -> 195 us,
-// the benchmark's 128 sequences of 512..4096 tokens 228 -> 229 us; with the non-temporal loads below the
-// edge has shrunk to 114 -> 113 us on the first, and the second is better off in the streaming shape).
+// kDepth - 1 cache blocks of 8 KiB are in flight per wavefront behind the one being worked on.  One
+// wavefront per SIMD: a second one buys nothing (the memory pipeline serves the older one first; a grid
+// of two workgroups per CU was 4% slower on batches of a thousand short sequences once the pipeline ran
+// through from piece to piece, and no faster on any other), and a fourth block in flight needs more
+// registers than the pipeline's state leaves (the compiler then parks fragments in AGPRs and copies
+// them back).
+constexpr int kDecodeDepth = 3;
 
 struct KVFrag {
   bf16x8 k[4];   // K block: unit (4*kk + quad, token = col)  ->  A operand of S^T step kk
@@ -133,16 +131,14 @@ __device__ __forceinline__ void process_block(KVFrag& f, const bf16x8 (&qf)[4], 
 // by ~3 us with every piece in its chunk), and some chunks hold a dozen pieces when others hold one.  So
 // that equal chunks are equal work, every (sequence, K/V head) is numbered with kPieceCost units in front
 // of its blocks that stand for that cost and hold no data (in units of a block's time).
-// (values from sweeps on five batch shapes: 2, 3, 4, 6 for the first - 512 sequences of ~400 tokens take
-// 159.6, 154.7, 154.1, 157.0 us - and 2, 3, 4 for the second - 1024 sequences of ~100 tokens 111.5, 109.0,
-// 108.1 us; the benchmark batches do not care)
-constexpr int kPieceCostStream = 4;  // one wavefront per SIMD
-constexpr int kPieceCostShared = 4;  // two per SIMD: a block takes about twice as much of a wavefront's time
+// (from sweeps on five batch shapes: with 2, 3, 4, 6 units 512 sequences of ~400 tokens take 159.6, 154.7,
+// 154.1, 157.0 us; the benchmark batches do not care)
+constexpr int kPieceCost = 4;
 
 // Exclusive prefix sums of the per-sequence unit counts (blocks + kPieceCost) into LDS: pre[b] = units
 // per K/V head of sequences 0..b-1, pre[B] = all; lens[b] = context length.  Called by all 256 threads.
 __device__ __forceinline__ void scan_block_counts(int* pre, int* lens, int* wsum, const int32_t* __restrict__ ctx_len,
-                                                  int B, int kPieceCost) {
+                                                  int B) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per = (B + kWaves * 64 - 1) / (kWaves * 64);
   const int b0 = tid * per;
@@ -203,8 +199,8 @@ struct Chunking {
 };
 constexpr int kMetaPre = 18;  // ws_meta: [0..7] c, [8..16] cum, then the batch prefix sums
 
-template <int kDepth, int kWgsPerCu>
-__global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
+template <int kDepth>
+__global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const uint16_t* __restrict__ q, int q_row_stride, const uint16_t* __restrict__ k_new,
     const uint16_t* __restrict__ v_new, int new_row_stride, const char* __restrict__ k_cache,
     const char* __restrict__ v_cache,
@@ -218,11 +214,10 @@ __global__ __launch_bounds__(kWaves * 64, kWgsPerCu) void decode_mfma_kernel(
   __shared__ int wsum[kWaves];
   __shared__ int s_c[8], s_cum[9];
   __shared__ __attribute__((aligned(16))) uint16_t s_new[kWaves][256];  // fused append: a token's K row, then its V row
-  constexpr int kOutBytes = kWgsPerCu == 2 ? 8192 : 16384;
+  constexpr int kOutBytes = 16384;
   __shared__ __attribute__((aligned(16))) char s_out[kWaves][kOutBytes];  // final results on their way out
   const long long t_start = wall_clock64();
-  constexpr int kPieceCost = kWgsPerCu == 2 ? kPieceCostShared : kPieceCostStream;
-  scan_block_counts(pre, lens, wsum, ctx_len, B, kPieceCost);
+  scan_block_counts(pre, lens, wsum, ctx_len, B);
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, quad = lane >> 4;
@@ -632,7 +627,6 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
   append_new_tokens(job, b * Hq + h, (int)(gridDim.x * gridDim.y));
   if (xcd_speed && b * Hq + h < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, b * Hq + h);
   const Chunking ch = {ws_meta, ws_meta + 8};
-  constexpr int kPieceCost = kPieceCostStream;  // (a forced split runs the one-per-SIMD shape)
   const int p0 = ws_meta[kMetaPre + b], nu = ws_meta[kMetaPre + b + 1] - p0;  // units: kPieceCost + blocks
   const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nu;
   const int n_split = ch.owner(seg_u0 + nu - 1) - ch.owner(seg_u0 + kPieceCost) + 1;
@@ -665,14 +659,14 @@ __global__ __launch_bounds__(64) void decode_cut_merge_kernel(const float* __res
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta,
                               int32_t ws_splits, const float* share_in, float* share_out, const float* xcd_speed,
-                              int32_t* ws_wave, int32_t* ws_cut, bool two_per_cu, hipStream_t s) {
+                              int32_t* ws_wave, int32_t* ws_cut, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   int n_wg = n_persistent_wgs;
   int c_forced = 0;
   if (split_tokens > 0) {
     // forced chunk size: the grid must cover the largest possible number of units
     c_forced = split_tokens / kBlockSize;
-    const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize + kPieceCostStream);
+    const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize + kPieceCost);
     const long long waves = (u_max + c_forced - 1) / c_forced;
     n_wg = (int)((waves + kWaves - 1) / kWaves);
     share_in = nullptr;
@@ -686,10 +680,7 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
                        (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out,
                        xcd_speed, ws_wave, ws_cut, a.B, a.Hq, a.Hkv, G, a.scale_log2e);
   };
-  if (two_per_cu)
-    launch(decode_mfma_kernel<3, 2>);
-  else
-    launch(decode_mfma_kernel<3, 1>);
+  launch(decode_mfma_kernel<kDecodeDepth>);
   return hipGetLastError();
 }
 

@@ -14,9 +14,7 @@ constexpr int kBlockSize = 16;        // tokens per cache block (the only suppor
 constexpr int kMaxGroup = 16;         // largest supported Hq / Hkv
 constexpr int kMinSplitTokens = 64;   // smallest decode split
 constexpr int kMaxSplitTokens = 4096; // largest forced decode split
-constexpr int kDecodeWgsPerCu = 1;    // persistent decode grid: workgroups per CU (one wavefront per SIMD) ...
-constexpr int kDecodeMaxWgsPerCu = 2; // ... two for a batch of many short (sequence, head) pieces
-constexpr int kDecodeManyPieces = 6;  // that is: this many (sequence, K/V head)s per wavefront of the one-per-CU grid
+constexpr int kDecodeWgsPerCu = 1;    // persistent decode grid: workgroups per CU (one wavefront per SIMD)
 constexpr int kMaxBatch = 4096;       // largest max_batch a context accepts (batch prefix sums live in LDS)
 constexpr int kPrefillTileRows = 128; // query rows of one prefill work item
 constexpr int kPrefillWgsPerCu = 2;   // persistent prefill grid: workgroups per CU
@@ -151,7 +149,7 @@ hipError_t launch_decode_merge(const AttnArgs& a, const int32_t* ctx_len, int32_
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
                               const float* share_in, float* share_out, const float* xcd_speed, int32_t* ws_wave,
-                              int32_t* ws_cut, bool two_per_cu, hipStream_t s);
+                              int32_t* ws_cut, hipStream_t s);
 // (with a.k_new given, the merge launch also stores every sequence's new token into the cache, position
 // ctx_len[b] - 1: the decode kernel has taken it from the new rows and left the cache alone)
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const int32_t* ctx_len, const float* ws_acc, const float* ws_ml,

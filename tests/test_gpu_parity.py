@@ -259,9 +259,10 @@ def test_append_at_the_largest_batch(dtype):
 
 def test_bf16_decode_of_hundreds_of_short_sequences():
     """800 sequences of 1..150 tokens with 8 K/V heads: more than six (sequence, head) pieces per
-    wavefront of the one-workgroup-per-CU grid, so the library launches its two-workgroups-per-CU shape,
-    and nearly every (sequence, head) is written in final form by the decode kernel while the merge
-    handles the few that a chunk boundary cuts.  Equal and measured per-XCD shares."""
+    wavefront, so the block pipeline crosses piece boundaries all the time, the results leave through the
+    LDS buffer in several batches, and nearly every (sequence, head) is written in final form by the
+    decode kernel while the merge handles the few that a chunk boundary cuts.  Equal and measured per-XCD
+    shares."""
     from paper_2504_18154_amd import binding
     model = M30
     rng = np.random.default_rng(47)
@@ -296,7 +297,7 @@ def test_decode_with_the_append_fused_in(shape):
     elif shape == "bf16-mha":
         model, lens = wl.ModelShape("mha", 6, 6, 128, 1, "bf16"), [0, 15, 16, 31, 32, 700]
     elif shape == "bf16-many-short":
-        model, lens = M30, list(np.random.default_rng(49).integers(0, 100, size=800))   # two workgroups per CU
+        model, lens = M30, list(np.random.default_rng(49).integers(0, 100, size=800))   # many pieces per wavefront
     elif shape == "bf16-forced-split":      # fixed chunks of 256 tokens: the other merge kernel carries the stores
         model, lens = M30, [0, 1, 15, 16, 255, 256, 600, 2047]
     else:
