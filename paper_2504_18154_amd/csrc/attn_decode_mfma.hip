@@ -280,8 +280,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
   // A piece: the blocks [blk0, blk0 + n) of one (sequence b, K/V head g) that fall into this
   // wavefront's chunk.  Everything a piece needs before its first K/V load - where it is
   // (LDS only), its query fragments and its first 64 block ids - is fetched while the
-  // previous piece is still streaming, so a change of piece costs one memory round trip
-  // (the refill of the block pipeline) instead of three.
+  // previous piece is still streaming, and so are its first blocks (see the pipeline below),
+  // so a change of piece costs no memory round trip.
   struct Piece {
     int b, g, blk0, n, nb, L;  // blocks [blk0, blk0 + n) of the nb blocks of (b, g); n == 0: the chunk ends before block 0
     long long seg_u0;          // first unit of (b, g): kPieceCost cost units, then its blocks
@@ -352,7 +352,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     bf16x8 qf[4];
     load_q(qf, cur);
     int ids = load_ids(cur, 0);
-    const size_t blk_stride_ = blk_stride;
     // Register pipeline kDepth blocks deep, running without a break through the whole chunk.  Blocks are
     // taken in windows of up to 64 (the ids one VGPR holds); a window of n blocks occupies np = n rounded
     // up to kDepth pipeline slots (the slots behind its last block do no work and their loads are loads of
@@ -366,7 +365,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
       const int n0 = min(64, cur.n);
 #pragma unroll
       for (int d = 0; d < kDepth - 1; ++d) {
-        const size_t off = (size_t)__builtin_amdgcn_readlane(ids, min(d, n0 - 1)) * blk_stride_ + (size_t)cur.g * 4096;
+        const size_t off = (size_t)__builtin_amdgcn_readlane(ids, min(d, n0 - 1)) * blk_stride + (size_t)cur.g * 4096;
         load_block(f[d], k_cache + off, v_cache + off, d < n0, lane, col, quad);
       }
     }
@@ -420,10 +419,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
               asm volatile("" ::: "memory");
               id = __builtin_amdgcn_readlane(ids_n, t - np);
             }
-            off = (size_t)id * blk_stride_ + nhead;
+            off = (size_t)id * blk_stride + nhead;
             live = true;
           } else {
-            off = (size_t)__builtin_amdgcn_readlane(my_id, min(t, n - 1)) * blk_stride_ + head_off;
+            off = (size_t)__builtin_amdgcn_readlane(my_id, min(t, n - 1)) * blk_stride + head_off;
           }
           load_block(fr, k_cache + off, v_cache + off, live, lane, col, quad);
         };
@@ -458,7 +457,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
         for (; i + 2 * kDepth - 1 <= n; i += kDepth) {
 #pragma unroll
           for (int d = 0; d < kDepth; ++d) {
-            const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, i + d + kDepth - 1) * blk_stride_ + head_off;
+            const size_t off = (size_t)__builtin_amdgcn_readlane(my_id, i + d + kDepth - 1) * blk_stride + head_off;
             load_block(f[(d + kDepth - 1) % kDepth], k_cache + off, v_cache + off, true, lane, col, quad);
             process_block(f[d], qf, acc, m, l, 16, quad, scale_log2e);
           }
