@@ -307,6 +307,28 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     p.L = lens[lo];
     return p;
   };
+  // The piece after p, which ended at the end of its (sequence, head) with units left in the chunk: the
+  // next K/V head, or head 0 of the next sequence - two LDS reads instead of a search.  A sequence without
+  // tokens (not a valid decode input, but it must not cost its neighbours their results) has no blocks and
+  // is passed over.
+  auto following = [&](const Piece& p) {
+    Piece q = p;
+    do {
+      const long long seg = q.seg_u0 + q.nb + kPieceCost;
+      if (++q.g == Hkv) {
+        q.g = 0;
+        ++q.b;
+      }
+      const int nu = pre[q.b + 1] - pre[q.b];
+      q.nb = nu - kPieceCost;
+      q.seg_u0 = seg;
+      q.u_stop = min(u_end, seg + nu);
+      q.blk0 = 0;
+      q.n = max((int)(q.u_stop - seg) - kPieceCost, 0);
+      q.L = lens[q.b];
+    } while (q.n == 0 && q.u_stop < u_end);
+    return q;
+  };
   // B operand of S^T: Q^T[d][head], heads beyond the group are zero columns
   auto load_q = [&](bf16x8 (&qf)[4], const Piece& p) {
     const uint16_t* qrow = q + (size_t)p.b * q_row_stride + ((size_t)p.g * G + col) * 128;
@@ -346,8 +368,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing but loads pending from here on
   };
 
-  long long u = u_begin;
-  Piece cur = locate(u);
+  Piece cur = locate(u_begin);
+  if (cur.n == 0 && cur.u_stop < u_end) cur = following(cur);  // (the chunk begins at an empty sequence)
   if (cur.n > 0) {  // (else: only the cost units of a (sequence, head) fall into this chunk)
     bf16x8 qf[4];
     load_q(qf, cur);
@@ -370,13 +392,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
       }
     }
     for (;;) {
-      const long long u_next = cur.u_stop;
-      const bool has_next = u_next < u_end;
+      const bool has_next = cur.u_stop < u_end;
       Piece nxt = cur;
       bf16x8 qn[4];
       int ids_n = 0;
       if (has_next) {
-        nxt = locate(u_next);
+        nxt = following(cur);
         load_q(qn, nxt);
         ids_n = load_ids(nxt, 0);
       }
@@ -518,7 +539,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (see flush)
       }
       if (!has_next || nxt.n == 0) break;  // n == 0: only the cost units of the next (sequence, head) are left
-      u = u_next;
       cur = nxt;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) qf[kk] = qn[kk];

@@ -286,6 +286,28 @@ def test_bf16_decode_of_hundreds_of_short_sequences():
     layer.close()
 
 
+def test_bf16_decode_passes_over_sequences_without_tokens():
+    """A context length of zero is not a valid decode input (the step's own token counts), but a batch that
+    holds one - first, last or in the middle, alone or several in a row - must not cost the other sequences
+    their results: their rows are held to the oracle, the empty sequences' rows are left alone."""
+    model = M30
+    lens = np.asarray([0, 700, 0, 0, 33, 257, 0, 1500, 16, 0], dtype=np.int32)
+    say(f"bf16 decode with empty sequences in the batch {lens.tolist()}")
+    pb, layer = _mk(model, np.maximum(lens, 1), seed=51)
+    _, k, v = _qkv(model, int(lens.sum()), 510)
+    layer.append(k, v, wl.cu_from_lengths(lens), np.zeros(len(lens), np.int32), pb.block_table)
+    q = wl.randn((len(lens), model.Hq, model.D), "bf16", 511)
+    live = np.flatnonzero(lens > 0)
+    ref, ref_lse = layer.decode_oracle(q[live], pb.block_table[live], lens[live])
+    from paper_2504_18154_amd import binding
+    for split in (0, 64):
+        layer.ctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, split)
+        out, lse = layer.decode_gpu(q, pb.block_table, lens, max_ctx_len=int(lens.max()))
+        compare(f"decode split={split}, rows of the non-empty sequences", out, ref, "bf16", rows=live)
+        compare_lse(f"decode split={split}", lse[torch.as_tensor(live, device=lse.device)], ref_lse, "bf16")
+    layer.close()
+
+
 @pytest.mark.parametrize("shape", ["bf16-G5", "bf16-mha", "bf16-many-short", "bf16-forced-split", "f32-plain"])
 def test_decode_with_the_append_fused_in(shape):
     """ecoserve_attn_decode_append against the two separate calls on a copy of the same cache: cache and
