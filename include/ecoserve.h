@@ -198,6 +198,8 @@ int ecoserve_attn_prefill(ecoserve_ctx* ctx, const void* q, const void* k_cache,
  * ctx_len[b] >= 1 counts it, and the query attends to keys 0..ctx_len[b]-1.
  * The context of a sequence is split across workgroups; partial softmax
  * states go through the context's workspace and are merged exactly.
+ * A sequence with ctx_len[b] == 0 has no defined result: its rows of out and
+ * lse hold unspecified values afterwards, the other sequences are unaffected.
  *
  *   q           : dev, E[B][Hq][D]
  *   ctx_len     : dev, int32[B]
