@@ -286,6 +286,55 @@ def test_bf16_decode_of_hundreds_of_short_sequences():
     layer.close()
 
 
+def test_bf16_decode_random_batches():
+    """Sixteen seeded random decode batches: group sizes 1..16, 1..8 K/V heads, 1..47 sequences whose lengths
+    mix a few tokens, a few hundred, about a thousand and up to five thousand, automatic and forced splits,
+    equal and measured shares, the plain call and the fused append + decode call (the last token of every
+    sequence wiped from the cache and handed in as the new one)."""
+    from paper_2504_18154_amd import binding
+    rng = np.random.default_rng(2025)
+    for case in range(16):
+        Hkv, G = int(rng.choice([1, 2, 8])), int(rng.choice([1, 4, 5, 8, 16]))
+        model = wl.ModelShape("random", Hkv * G, Hkv, 128, 1, "bf16")
+        B = int(rng.integers(1, 48))
+        kind = rng.integers(0, 4, size=B)
+        lens = np.where(kind == 0, rng.integers(1, 40, size=B),
+                        np.where(kind == 1, rng.integers(40, 700, size=B),
+                                 np.where(kind == 2, rng.integers(1000, 1100, size=B),
+                                          rng.integers(1, 5000, size=B)))).astype(np.int32)
+        while int(lens.sum()) * model.Hq > 2_000_000:   # keeps the oracle's share of the test short
+            lens = np.maximum(lens // 2, 1)
+        split, adaptive, fused = int(rng.choice([0, 0, 64, 256, 1024])), int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        say(f"random decode batch {case}: Hq {model.Hq} Hkv {Hkv} B {B} tokens {int(lens.sum())} max {int(lens.max())} "
+            f"split {split} measured shares {adaptive} fused {fused}")
+        pb, layer = _mk(model, lens, seed=900 + case)
+        _, k, v = _qkv(model, pb.T, 910 + 3 * case)
+        layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+        layer.ctx.set_option(binding.OPT_DECODE_SPLIT_TOKENS, split)
+        layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, adaptive)
+        q = wl.randn((B, model.Hq, model.D), "bf16", 990 + case)
+        ref, ref_lse = layer.decode_oracle(q, pb.block_table, lens)
+        table, ctx_dev = dev_i32(pb.block_table), dev_i32(lens)
+        for rep in range(3 if adaptive else 1):
+            if fused:
+                last = torch.as_tensor(pb.cu_q[1:] - 1, dtype=torch.int64)
+                kn, vn = k[last].contiguous().cuda(), v[last].contiguous().cuda()
+                wipe = torch.full_like(kn, float("nan"))
+                layer.ctx.kv_append(layer.kc, layer.vc, wipe, wipe, dev_i32(wl.cu_from_lengths([1] * B)),
+                                    dev_i32(lens - 1), table, max_new_len=1)
+                out = torch.full((B, model.Hq, model.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+                lse = torch.full((B, model.Hq), float("nan"), dtype=torch.float32, device="cuda")
+                layer.ctx.attn_decode_append(q.cuda(), kn, vn, layer.kc, layer.vc, table, ctx_dev, out,
+                                             int(lens.max()), lse)
+                torch.cuda.synchronize()
+                layer.assert_cache_bit_exact()
+            else:
+                out, lse = layer.decode_gpu(q, pb.block_table, lens)
+            compare(f"batch {case} call {rep}", out, ref, "bf16")
+            compare_lse(f"batch {case} call {rep}", lse, ref_lse, "bf16")
+        layer.close()
+
+
 def test_bf16_decode_passes_over_sequences_without_tokens():
     """A context length of zero is not a valid decode input (the step's own token counts), but a batch that
     holds one - first, last or in the middle, alone or several in a row - must not cost the other sequences
