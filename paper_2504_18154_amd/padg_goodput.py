@@ -176,23 +176,51 @@ def main() -> int:
         line = {"dataset": ds, "instances": args.instances, "slo_ttft_s": slo[0] / 1e6, "slo_tpot_ms": slo[1] / 1e3}
         for name, search_all in (("algorithm1_as_printed", False), ("algorithm1_cyclic_search", True)):
             kw = dict(base_kw, search_all=search_all)
-            # bracket the 90% point: double the rate until attainment drops below 0.9, then bisect
-            lo, hi, curve = 0.0, 1.0, []
-            while hi < 1e5:
-                a = attainment(kw, poisson_stream(ds, args.requests, hi, 77), slo)
-                curve.append((hi, a))
-                if a < 0.9:
+            # The attainment curve need not fall monotonically (a moderate rate can switch phases at an unlucky
+            # rhythm and dip, a higher one batches better and recovers), so the 90% point is looked for from
+            # above: rates on a geometric grid until attainment has collapsed, the largest grid rate that
+            # still attains 90%, then a bisection between it and the next grid point.
+            att = lambda r: attainment(kw, poisson_stream(ds, args.requests, r, 77), slo)
+            curve, rate = [], 1.0
+            while rate < 1e5:
+                a = att(rate)
+                curve.append((rate, a))
+                if a < 0.5:
                     break
-                lo, hi = hi, hi * 2
-            for _ in range(12):
+                rate *= 1.25
+            grid_points = list(curve)
+            good = [i for i, (_, a) in enumerate(curve) if a >= 0.9]
+            lo = curve[good[-1]][0] if good else 0.0
+            hi = curve[good[-1] + 1][0] if good and good[-1] + 1 < len(curve) else (curve[0][0] if not good else lo)
+            for _ in range(10):
+                if hi <= lo:
+                    break
                 mid = 0.5 * (lo + hi)
-                a = attainment(kw, poisson_stream(ds, args.requests, mid, 77), slo)
+                a = att(mid)
                 curve.append((mid, a))
                 if a >= 0.9:
                     lo = mid
                 else:
                     hi = mid
+            # ... and from below: the rate up to which every grid rate attains 90% (equal to the above if the
+            # curve has no dip), refined the same way
+            first_bad = next((i for i, (_, a) in enumerate(grid_points) if a < 0.9), None)
+            lo1 = grid_points[first_bad - 1][0] if first_bad else (0.0 if first_bad == 0 else lo)
+            hi1 = grid_points[first_bad][0] if first_bad else lo1
+            for _ in range(10):
+                if hi1 <= lo1 or first_bad is None:
+                    break
+                mid = 0.5 * (lo1 + hi1)
+                a = att(mid)
+                curve.append((mid, a))
+                if a >= 0.9:
+                    lo1 = mid
+                else:
+                    hi1 = mid
+            below = [a for r, a in curve if r <= lo]
             line[name] = {"goodput_req_per_s": lo, "goodput_per_instance": lo / args.instances,
+                          "goodput_without_dip_req_per_s": min(lo1, lo),
+                          "lowest_attainment_below_goodput": min(below) if below else None,
                           "curve": sorted((round(r, 3), round(a, 4)) for r, a in curve)}
         print(json.dumps(line), flush=True)
     return 0
