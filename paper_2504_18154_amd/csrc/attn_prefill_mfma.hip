@@ -19,6 +19,9 @@
 // first in the K/V head, and a workgroup serves the items whose index is congruent to its
 // XCD (workgroup ids are dealt round-robin to the 8 XCDs): with 8 K/V heads each XCD's L2
 // holds one head's K/V.
+// A prompt of at most 128 / G new tokens (G = query heads per K/V head) gets a packed tile
+// instead: its rows are (query head of the group, position), so one item serves all G heads
+// over the same K/V (see the plan kernel).
 //
 // Per 64-key step the four 16-token cache blocks of K and of V go straight from global
 // memory into LDS (global_load ... lds, 16 bytes per lane, double buffered, one barrier per
@@ -175,7 +178,8 @@ __device__ __forceinline__ void exp_tile(const f32x16& s, bf16x8 (&pf)[2], float
 
 // ---- plan: the query tiles of a batch, heaviest first ------------------------------------------
 //
-// Plan layout (int32): [0] number of query tiles, [kPlanCounter0 + kPlanCounterStride * (kQueues * p
+// Plan layout (int32): [0] number of query tiles, [1] positions per packed tile and their reciprocal (0: no tile can be packed), [2] number of ordinary tiles (the packed ones follow them),
+// [kPlanCounter0 + kPlanCounterStride * (kQueues * p
 // + i)] ticket counter of work queue i in counter set p (one cache line each; launches alternate
 // between the two sets and each launch leaves the other set ready for the next, so a tile list can
 // serve many launches without being rebuilt), then from kPlanHeaderInts one record of kRecInts per
@@ -189,9 +193,9 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
                                                                     const int32_t* __restrict__ ctx_before,
                                                                     const int32_t* __restrict__ block_table,
                                                                     int bt_stride, int B, int n_main_wgs,
-                                                                    int max_tiles, int32_t* __restrict__ plan) {
+                                                                    int max_tiles, int G, int32_t* __restrict__ plan) {
   __shared__ int pre[kMaxBatch + 1];
-  __shared__ int bins[kPlanBins];
+  __shared__ int bins[2 * kPlanBins];  // weight classes of the ordinary tiles, then of the packed ones
   __shared__ int wsum[kPlanThreads / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // exclusive prefix of one value per thread over the workgroup; `total` receives the sum
@@ -219,6 +223,11 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
   int local = 0;
   for (int i = 0; i < per; ++i)
     if (b0 + i < B) local += tiles_of(b0 + i);
+  // Packed tiles: a prompt with at most P = kTQ / G new tokens fits a tile G times over, so its tile holds
+  // all G query heads of a K/V head (row = head * P + position) and one item does what G items would, over
+  // the same staged K/V: hundreds of 20-token prompts are otherwise one item per (prompt, query head) with a
+  // sixth of its rows in use.  Packed tiles are listed behind the ordinary ones.
+  const int P = G > 1 ? kTQ / G : 0;
   int n_tiles_all;
   int run = block_scan(local, n_tiles_all);
   // never more records than the host sized the launch (and the plan buffer) for, whatever cu_q says
@@ -229,7 +238,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
       run += tiles_of(b0 + i);
     }
   if (tid == 0) pre[B] = n_tiles_all;
-  for (int i = tid; i < kPlanBins; i += kPlanThreads) bins[i] = 0;
+  for (int i = tid; i < 2 * kPlanBins; i += kPlanThreads) bins[i] = 0;
   __syncthreads();
 
   // tile i of the batch (sequence after sequence) -> sequence, tile, key steps, weight class
@@ -244,7 +253,8 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     const int S = cu_q[b + 1] - cu_q[b];
     const long long kv_end = (long long)ctx_before[b] + (long long)qt * kTQ + min(kTQ, S - qt * kTQ);
     steps = (int)((kv_end + kTK - 1) / kTK);
-    return kPlanBins - 1 - min(steps, kPlanBins - 1);  // class 0 = heaviest
+    const int cls = kPlanBins - 1 - min(steps, kPlanBins - 1);  // class 0 = heaviest
+    return S <= P ? kPlanBins + cls : cls;
   };
   for (int i = tid; i < n_tiles_all; i += kPlanThreads) {
     int b, qt, steps;
@@ -252,7 +262,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
   }
   __syncthreads();
   {
-    constexpr int kPer = kPlanBins / kPlanThreads;
+    constexpr int kPer = 2 * kPlanBins / kPlanThreads;
     int cnt[kPer], sum = 0;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
@@ -266,6 +276,11 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
       bins[tid * kPer + i] = start;
       start += cnt[i];
     }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    plan[1] = P ? (P | ((65536 / P + 1) << 8)) : 0;
+    plan[2] = bins[kPlanBins];  // number of ordinary tiles = where the packed ones begin
   }
   __syncthreads();
   for (int i = tid; i < n_tiles_all; i += kPlanThreads) {
@@ -291,8 +306,10 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
 }
 
 // Wave-uniform description of one work item (a query tile of one query head).
+constexpr int kPackedItem = 1 << 30;  // flag in the query head number handed to describe(): a packed tile
 struct Item {
   int tok0, S, cb, q0, g, h, n_tiles;
+  bool pk;  // packed tile: rows are (query head h + row / P, position row % P)
   const int32_t* bt_row;
   __device__ __forceinline__ int L_total() const { return cb + S; }
   __device__ __forceinline__ int nblk_total() const { return (cb + S + 15) >> 4; }
@@ -308,12 +325,14 @@ __device__ __forceinline__ Item describe(int rec, int g, int h, const int32_t* _
   t.cb = __builtin_amdgcn_readlane(rec, 4);
   t.n_tiles = __builtin_amdgcn_readlane(rec, 5);
   t.g = g;
-  t.h = h;
+  t.h = h & (kPackedItem - 1);
+  t.pk = (h & kPackedItem) != 0;
   t.q0 = qt * kTQ;
   t.bt_row = block_table + (size_t)b * bt_stride;
   return t;
 }
 
+template <bool kMayPack>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     const uint16_t* __restrict__ q, int q_row_stride, const char* __restrict__ k_cache,
     const char* __restrict__ v_cache, const int32_t* __restrict__ block_table, int bt_stride,
@@ -331,8 +350,15 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
                              // load: an outstanding scalar load would force full waits on every LDS read)
   const float c = scale_log2e;
   const size_t blk_stride = (size_t)Hkv * 4096;
-  const int heads = G * Hkv;
-  const int n_flat = plan[0] * heads;
+  // Packed tiles: P positions per tile (row = head * P + position) in the low byte, above it p_inv with
+  // row / P == (row * p_inv) >> 16 for rows 0..127.  kMayPack false: every tile is taken as an ordinary one
+  // and none of the packing code is compiled in (this kernel has no register to spare for it; the launcher
+  // picks that variant for batches of long prompts); true: the tiles the plan lists as packed are.
+  const int packing = kMayPack ? plan[1] : 0;
+  const int heads = G * Hkv;  // items of an ordinary tile
+  const int n_ord_tiles = packing ? plan[2] : plan[0];
+  const int n_ordinary = n_ord_tiles * heads;  // items of the ordinary tiles; one per K/V head of the packed ones follow
+  const int n_flat = n_ordinary + (plan[0] - n_ord_tiles) * Hkv;
   const int32_t* const recs = plan + kPlanHeaderInts;
   // Work items are dealt to kQueues queues (item f belongs to queue f % kQueues) and workgroup w
   // serves queue w % kQueues.  kQueues is a multiple of 8: workgroup ids are dealt round-robin to
@@ -355,6 +381,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   // item f is query head f % (G Hkv) of tile f / (G Hkv), the K/V head varying fastest
   int tile_of_f, g_of_f, h_of_f;
   auto split = [&](int f) {
+    if (kMayPack && f >= n_ordinary) {  // a packed tile: one item per K/V head, its G query heads share it
+      const int fp = f - n_ordinary, t = fast_div(fp, div_hkv);
+      tile_of_f = n_ord_tiles + t;
+      g_of_f = fp - t * Hkv;
+      h_of_f = (g_of_f * G) | kPackedItem;
+      return;
+    }
     tile_of_f = fast_div(f, div_heads);
     const int hp = f - tile_of_f * heads;
     const int hg = fast_div(hp, div_hkv);
@@ -384,15 +417,29 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   int g_next = 0, h_next = 0;                    // heads of the next item
 
   // per-lane view of the current item
-  int row, pos, w_pmin, n_w;
-  bool row_valid;
+  int pos, w_pmin, n_w;
   size_t head_off;
+  // tile row -> (query row inside the sequence, query head inside the group, row in use)
+  auto map_row = [&](const Item& t, int& r, int& hq, bool& ok) {
+    const int rr = wave * 32 + col;
+    if (kMayPack && t.pk) {
+      hq = (rr * (packing >> 8)) >> 16;
+      r = rr - hq * (packing & 255);
+      ok = hq < G && r < t.S;
+    } else {
+      hq = 0;
+      r = t.q0 + rr;
+      ok = r < t.S;
+    }
+  };
   auto enter = [&](const Item& t) {
-    row = t.q0 + wave * 32 + col;                          // this lane's query row inside the sequence
-    row_valid = row < t.S;
+    int row, hsel;
+    bool row_valid;
+    map_row(t, row, hsel, row_valid);
     pos = t.cb + row;                                      // absolute position = causal bound
-    w_pmin = t.cb + t.q0 + wave * 32;                      // smallest / largest bound in this wavefront
-    const int w_pmax = t.cb + min(t.S - 1, t.q0 + wave * 32 + 31);
+    // smallest / largest bound in this wavefront (packed: of the tile, every wavefront sees every position)
+    w_pmin = kMayPack && t.pk ? t.cb : t.cb + t.q0 + wave * 32;
+    const int w_pmax = kMayPack && t.pk ? t.cb + t.S - 1 : t.cb + min(t.S - 1, t.q0 + wave * 32 + 31);
     n_w = min(t.n_tiles, w_pmax / kTK + 1);                // steps not wholly above this wavefront's diagonal
     head_off = (size_t)t.g * 4096;
   };
@@ -401,9 +448,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   // B operand of S^T: Q^T[d][row]; step t covers d = 16 t .. 16 t + 15
   bf16x8 qf[8];
   auto load_q = [&](const Item& t) {
-    const int r = t.q0 + wave * 32 + col;
-    const uint16_t* qrow = q + (size_t)(t.tok0 + r) * q_row_stride + t.h * 128 + half * 8;
-    const bool ok = r < t.S;
+    int r, hq;
+    bool ok;
+    map_row(t, r, hq, ok);
+    const uint16_t* qrow = q + (size_t)(t.tok0 + r) * q_row_stride + (t.h + hq) * 128 + half * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -632,7 +680,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
       // The two lanes of a row exchange halves (one v_permlane32_swap per register pair) so that
       // the lower lane holds the 16 bytes of d = 32 dt + 16 p .. + 7 and the upper lane the next 16.
       const float inv = 1.f / l;
-      uint16_t* orow = out + ((size_t)(cur.tok0 + row) * Hq + cur.h) * 128 + half * 8;
+      int row, hsel;  // (worked out again rather than kept in registers through the item)
+      bool row_valid;
+      map_row(cur, row, hsel, row_valid);
+      uint16_t* orow = out + ((size_t)(cur.tok0 + row) * Hq + cur.h + hsel) * 128 + half * 8;
       auto pack = [&](float a, float b) {
         const bf16x2 v = {(__bf16)(a * inv), (__bf16)(b * inv)};
         return __builtin_bit_cast(uint32_t, v);
@@ -654,8 +705,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
           if (row_valid) *reinterpret_cast<u32x4*>(orow + dt * 32 + p * 16) = w;
         }
     }
-    if (row_valid) {
-      if (lse && half == 0) lse[(size_t)(cur.tok0 + row) * Hq + cur.h] = (m * c + log2f(l)) * kLn2;
+    if (lse && half == 0) {
+      int row, hsel;
+      bool row_valid;
+      map_row(cur, row, hsel, row_valid);
+      if (row_valid) lse[(size_t)(cur.tok0 + row) * Hq + cur.h + hsel] = (m * c + log2f(l)) * kLn2;
     }
     if (f_next < 0) break;
 
@@ -685,7 +739,7 @@ int32_t prefill_mfma_grid(const AttnArgs& a, int32_t T, int32_t n_persistent_wgs
 }
 
 hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int32_t* ctx_before, int32_t T,
-                               int32_t /*max_q_len*/, int32_t* ws_plan, int32_t n_persistent_wgs, bool make_plan,
+                               int32_t max_q_len, int32_t* ws_plan, int32_t n_persistent_wgs, bool make_plan,
                                int parity, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   const int64_t max_tiles = prefill_plan_tiles(a.B, T);
@@ -694,12 +748,20 @@ hipError_t launch_prefill_mfma(const AttnArgs& a, const int32_t* cu_q, const int
   if (n_wg < 0) return hipErrorInvalidValue;
   if (make_plan)
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, cu_q, ctx_before, a.block_table,
-                       a.bt_stride, a.B, (int)n_wg, (int)max_tiles, ws_plan);
-  hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q,
-                     a.q_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
-                     a.lse, ws_plan, parity, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)),
-                     make_divisor((uint32_t)a.Hkv),
-                     a.scale_log2e);
+                       a.bt_stride, a.B, (int)n_wg, (int)max_tiles, G, ws_plan);
+  auto launch = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_wg), dim3(256), 0, s, (const uint16_t*)a.q, a.q_row_stride,
+                       (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, (uint16_t*)a.out,
+                       a.lse, ws_plan, parity, a.Hq, a.Hkv, G, make_divisor((uint32_t)(G * a.Hkv)),
+                       make_divisor((uint32_t)a.Hkv), a.scale_log2e);
+  };
+  // The variant that can pack short prompts' tiles for batches that may hold many of them (few new tokens
+  // per sequence on average); which tiles are packed is decided by the tile list, from the lengths themselves.
+  (void)max_q_len;
+  if (G > 1 && (int64_t)T <= (int64_t)a.B * 2 * (kTQ / G))
+    launch(prefill_mfma_kernel<true>);
+  else
+    launch(prefill_mfma_kernel<false>);
   return hipGetLastError();
 }
 

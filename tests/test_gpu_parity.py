@@ -71,6 +71,41 @@ def test_bf16_prefill_ragged_lengths(model):
     layer.close()
 
 
+@pytest.mark.parametrize("heads", [(40, 8), (64, 8), (32, 2), (8, 2), (6, 6)], ids=["G5", "G8", "G16", "G4", "G1"])
+def test_bf16_prefill_of_short_prompts_in_packed_tiles(heads):
+    """Prompts that fit kTQ / G rows (25 new tokens for G = 5): the library packs the G query
+    heads of a K/V head into one tile.  Lengths 0 .. P including both ends, with and without a cached prefix
+    (then the packed rows sit behind hundreds of cached keys); a prompt that breaks the rule by one token and
+    takes ordinary tiles beside packed ones; and sixty-three prompts of mixed lengths, one of them two tiles
+    long.  The caller's bound on the lengths is exact, too small and generous in turn: it decides nothing."""
+    model = wl.ModelShape("short", heads[0], heads[1], 128, 1, "bf16")
+    G = heads[0] // heads[1]
+    P = 128 // G
+    rng = np.random.default_rng(77 + G)
+    for name, new, prefix in (
+            ("no prefix", np.r_[0, 1, P, P - 1, rng.integers(1, P + 1, size=37)], None),
+            ("cached prefix", np.r_[P, 1, rng.integers(1, P + 1, size=10)], np.r_[300, 17, rng.integers(0, 400, size=10)]),
+            ("one token too long", np.r_[3, P + 1, 5, min(P, 9)], None),
+            ("short and longer prompts mixed", np.r_[rng.integers(1, 3 * P, size=60), 140, 1, P], np.r_[rng.integers(0, 90, size=60), 0, 5, 64])):
+        new = new.astype(np.int32)
+        prefix = np.zeros_like(new) if prefix is None else prefix.astype(np.int32)
+        say(f"bf16 prefill of short prompts, G = {G} (P = {P}), {name}: new {new.tolist()}")
+        pb, layer = _mk(model, np.maximum(prefix + new, 1), seed=80 + G)
+        if prefix.sum() > 0:
+            _, k1, v1 = _qkv(model, int(prefix.sum()), 800 + G)
+            layer.append(k1, v1, wl.cu_from_lengths(prefix), np.zeros_like(prefix), pb.block_table)
+        cu = wl.cu_from_lengths(new)
+        q, k2, v2 = _qkv(model, int(new.sum()), 810 + G)
+        layer.append(k2, v2, cu, prefix, pb.block_table)
+        layer.assert_cache_bit_exact()
+        ref, ref_lse = layer.prefill_oracle(q, cu, prefix, pb.block_table)
+        for bound in (int(new.max()), min(P, int(new.max())), min(128, int(new.sum()))):   # exact, as small as packing needs, generous
+            out, lse = layer.prefill_gpu(q, cu, prefix, pb.block_table, max_q_len=bound)
+            compare(f"prefill, max_q_len = {bound}", out, ref, "bf16")
+            compare_lse(f"prefill, max_q_len = {bound}", lse, ref_lse, "bf16")
+        layer.close()
+
+
 def test_bf16_prefill_with_cached_prefix():
     """Second chunk of a prompt: queries sit at ctx_before + i and see the prefix too."""
     model = M30
