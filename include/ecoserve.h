@@ -180,7 +180,8 @@ int ecoserve_kv_append(ecoserve_ctx* ctx, void* k_cache, void* v_cache, const vo
  *   k_cache, v_cache, cu_q, ctx_before, block_table, bt_stride, B, T : as in ecoserve_kv_append
  *   out         : dev, E[T][Hq][D] (rounded to E with round-to-nearest-even)
  *   lse         : dev, float[T][Hq] natural-log sum-exp of the scaled scores, or NULL
- *   max_q_len   : upper bound on any sequence's new-token count (sizes the launch)
+ *   max_q_len   : upper bound on any sequence's new-token count, in 1..T (checked; the kernels
+ *                 take every length from cu_q, so a loose bound costs nothing)
  *   Sequences with zero new tokens are skipped.  B == 0 or T == 0 is a no-op.
  *   T / 128 + min(B, T) must not exceed num_blocks / 8 + max_batch (a batch cannot bring more
  *   new tokens than the pool holds; the context's list of query tiles is sized for that), else
