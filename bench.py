@@ -133,6 +133,19 @@ def sweep() -> int:
     decode("multi-head model (52 q = 52 kv heads), 128 seqs, ctx U[512,4096]",
            wl.decode_batch(wl.M30B_MHA, 128, 512, 4096, 7), layers=2)
     decode("30B, 16 seqs, ctx U[512,4096] (small batch)", wl.decode_batch(wl.M30B, 16, 512, 4096, 6))
+
+    def consecutive(db):
+        """The same batch over a block table that gives every sequence consecutive physical blocks (a fresh allocator)."""
+        table = np.array(db.block_table)
+        first = 0
+        for b, n in enumerate((np.asarray(db.ctx_len) + db.model.bs - 1) // db.model.bs):
+            table[b, :n] = np.arange(first, first + n)
+            first += n
+        return wl.DecodeBatch(db.model, db.ctx_len, table.astype(np.int32), db.num_blocks, db.seed)
+
+    decode("30B decode batch of config 1 over consecutive physical blocks", consecutive(wl.config2_decode_30b()))
+    decode("30B, 128 seqs, every context 8192, over consecutive physical blocks",
+           consecutive(wl.decode_batch(wl.M30B, 128, 8192, 8192, 5)))
     decode("30B, 512 seqs, contexts shaped like ShareGPT (Table 4)", wl.table4_decode_batch(wl.M30B, "sharegpt", 512, 21))
     decode("30B, 1024 seqs, contexts shaped like Alpaca (Table 4)", wl.table4_decode_batch(wl.M30B, "alpaca", 1024, 22))
     decode("30B, 64 seqs, contexts shaped like LongBench (Table 4)", wl.table4_decode_batch(wl.M30B, "longbench", 64, 23))
