@@ -351,9 +351,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const uint32_t h = ((uint32_t)p.b * 0x9E3779B1u + (uint32_t)p.g * 0x85EBCA77u) >> 8;
     return (int)(((unsigned long long)(h & 0xffffffu) * (unsigned)(p.n - 1)) >> 24);  // in [0, n - 1), 0 for n = 1
   };
-  auto step_of = [&](const Piece& p) {  // 1 for short pieces, else the first of 37, 41, 43 that does not divide n - 1
+  auto step_of = [&](const Piece& p) {  // the first of 37, 41, 43 (7, 5, 11 for short pieces) that does not divide n - 1
     const int m = p.n - 1;
-    if (m <= 40) return 1;
+    if (m <= 12) return 1;
+    if (m <= 40) return m % 7 != 0 ? 7 : m % 5 != 0 ? 5 : 11;
     return m % 37 != 0 ? 37 : m % 41 != 0 ? 41 : 43;
   };
   auto block_at = [&](const Piece& p, int start, int step, int i) {  // i in [0, n)
