@@ -100,15 +100,16 @@ def test_config3_prefill_30b_one_layer_sampled_rows():
     layer.close()
 
 
-def test_alpaca_shaped_prefill_and_decode_batches_in_full():
-    """The batches `bench.py --sweep` times for the paper's chat workload (Table 4, Alpaca: some twenty input
-    tokens, some sixty output tokens): 512 short prompts prefilled in one batch - most of them in packed tiles,
-    the tail of the length distribution in ordinary ones - and the decode step of 1024 such sequences, many
-    (sequence, head) pieces per wavefront.  Every output row against the oracle."""
+@pytest.mark.parametrize("dataset, seed, n_prefill, n_decode, decode_seed", [("alpaca", 32, 512, 1024, 22), ("sharegpt", 31, 64, 512, 21)])
+def test_chat_shaped_prefill_and_decode_batches_in_full(dataset, seed, n_prefill, n_decode, decode_seed):
+    """The batches `bench.py --sweep` times for the paper's chat workloads (Table 4; Alpaca: some twenty input
+    tokens, some sixty output tokens): the prompts prefilled in one batch - of the Alpaca-shaped ones most in
+    packed tiles, the tail of the length distribution in ordinary ones - and the decode step of twice as many
+    such sequences, many (sequence, head) pieces per wavefront.  Every output row against the oracle."""
     model = wl.M30B
-    q_len = wl.table4_lengths("alpaca", wl.rng_for(32), 512)[0]
+    q_len = wl.table4_lengths(dataset, wl.rng_for(seed), n_prefill)[0]
     pb = wl.prefill_batch(model, q_len, 3)
-    say(f"Alpaca-shaped prefill: {pb.B} prompts, {pb.T} tokens, {int((np.asarray(q_len) <= 25).sum())} of them at most 25 long")
+    say(f"{dataset}-shaped prefill: {pb.B} prompts, {pb.T} tokens, {int((np.asarray(q_len) <= 25).sum())} of them at most 25 long")
     layer = Layer(model, pb.num_blocks, pb.B, pb.block_table.shape[1])
     k, v = _stream(model, pb.T, 41)
     q = wl.randn((pb.T, model.Hq, model.D), "bf16", 43, device="cuda")
@@ -116,10 +117,10 @@ def test_alpaca_shaped_prefill_and_decode_batches_in_full():
     layer.assert_cache_bit_exact()
     out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table, max_q_len=pb.max_q_len)
     ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
-    compare("Alpaca-shaped prefill", out, ref, "bf16")
-    compare_lse("Alpaca-shaped prefill", lse, ref_lse, "bf16")
+    compare(f"{dataset}-shaped prefill", out, ref, "bf16")
+    compare_lse(f"{dataset}-shaped prefill", lse, ref_lse, "bf16")
     layer.close()
-    _decode_full(wl.table4_decode_batch(model, "alpaca", 1024, 22), "Alpaca-shaped decode batch")
+    _decode_full(wl.table4_decode_batch(model, dataset, n_decode, decode_seed), f"{dataset}-shaped decode batch")
 
 
 def test_config5_switch_70b_one_layer():
