@@ -629,13 +629,22 @@ struct AppendJob {
 __device__ __forceinline__ void append_new_tokens(const AppendJob& j, int bid, int n_blocks) {
   if (j.k_new == nullptr) return;
   for (int pair = bid; pair < j.B * j.Hkv; pair += n_blocks) {
-    const int b = pair / j.Hkv, g = pair % j.Hkv;
+    const int b = pair / j.Hkv, g = pair % j.Hkv, lane = (int)threadIdx.x;
+    // the token's rows are asked for first: they do not depend on where the token goes, and the two
+    // dependent reads that tell (length, block table) are then answered alongside them
+    const size_t row = (size_t)b * j.new_row_stride + (size_t)g * 128;
+    u32x4 kval = {0u, 0u, 0u, 0u};
+    if (lane < 16) kval = *reinterpret_cast<const u32x4*>(j.k_new + row + lane * 8);
+    const uint16_t v0 = j.v_new[row + lane], v1 = j.v_new[row + 64 + lane];
     const int p = j.ctx_len[b] - 1;
     if (p < 0) continue;  // an empty sequence has no new token (and no output row worth reading)
     const int64_t blk = j.block_table[(size_t)b * j.bt_stride + (p >> 4)];
-    const size_t row = (size_t)b * j.new_row_stride + (size_t)g * 128;
-    append_one_row<uint16_t>(j.k_cache, j.v_cache, j.k_new + row, j.v_new + row, blk, g, p & 15, j.Hkv, 128,
-                             (int)threadIdx.x);
+    const int slot = p & 15;
+    const size_t base = ((size_t)blk * j.Hkv + g) * 2048;  // elements of one (block, head): 16 slots x 128
+    // K: unit c of the row goes to [c][slot][8 elements]; V: element d to [d][slot]
+    if (lane < 16) *reinterpret_cast<u32x4*>(j.k_cache + base + (size_t)lane * 128 + slot * 8) = kval;
+    j.v_cache[base + (size_t)lane * 16 + slot] = v0;
+    j.v_cache[base + (size_t)(64 + lane) * 16 + slot] = v1;
   }
 }
 
