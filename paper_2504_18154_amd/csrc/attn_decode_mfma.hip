@@ -655,14 +655,36 @@ __device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc,
                                                float* __restrict__ lse_out) {
   const int lane = threadIdx.x;
   float M = -INFINITY;
-  for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[(base + k) * 2]);
   float lsum = 0.f, o0 = 0.f, o1 = 0.f;
-  for (int k = 0; k < n_split; ++k) {
-    const float w = exp2f(ws_ml[(base + k) * 2] - M);
-    lsum += ws_ml[(base + k) * 2 + 1] * w;
-    const float2 a = *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane);
-    o0 += a.x * w;
-    o1 += a.y * w;
+  if (n_split <= 4) {
+    // the usual case (a chunk boundary or two inside the sequence): every state is asked for at once
+    float mk[4], lk[4];
+    float2 ak[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bool in = k < n_split;
+      mk[k] = in ? ws_ml[(base + k) * 2] : -INFINITY;
+      lk[k] = in ? ws_ml[(base + k) * 2 + 1] : 0.f;
+      ak[k] = in ? *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane) : float2{0.f, 0.f};
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) M = fmaxf(M, mk[k]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float w = k < n_split ? exp2f(mk[k] - M) : 0.f;
+      lsum += lk[k] * w;
+      o0 += ak[k].x * w;
+      o1 += ak[k].y * w;
+    }
+  } else {
+    for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[(base + k) * 2]);
+    for (int k = 0; k < n_split; ++k) {
+      const float w = exp2f(ws_ml[(base + k) * 2] - M);
+      lsum += ws_ml[(base + k) * 2 + 1] * w;
+      const float2 a = *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane);
+      o0 += a.x * w;
+      o1 += a.y * w;
+    }
   }
   const float inv = 1.f / lsum;
   const uint32_t w = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
