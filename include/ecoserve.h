@@ -118,7 +118,10 @@ enum {
    * batch - the caller vouches that the arrays' contents have not changed - and share the list
    * of query tiles that the first of them builds, instead of each building its own (the layers
    * of one step of a model: the list depends only on these arrays).  0 (default): every call
-   * builds its list.  Setting the option, to either value, forgets the current list. */
+   * builds its list.  Setting the option, to either value, forgets the current list: a caller
+   * whose allocator may hand the same addresses to a new batch sets it again at every step.
+   * With the option on, ecoserve_attn_prefill on a stream that is being captured returns
+   * ECOSERVE_EINVAL (a recorded launch cannot decide at replay whether its list is current). */
   ECOSERVE_OPT_PREFILL_REUSE_PLAN = 5
 };
 
@@ -161,7 +164,8 @@ size_t ecoserve_workspace_bytes(const ecoserve_ctx* ctx);
  *   ctx_before       : dev, int32[B], tokens of each sequence already cached
  *   block_table      : dev, int32[B][bt_stride]; entries beyond a sequence's blocks are never read
  *   B, T             : batch size and total new tokens (B <= max_batch); B == 0 or T == 0 is a no-op
- *   max_new_len      : upper bound on any sequence's new-token count (sizes the launch)
+ *   max_new_len      : upper bound on any sequence's new-token count, in 1..T (sizes the launch;
+ *                      <= 1 selects the one-token-per-sequence kernel); 0 with T > 0: ECOSERVE_EINVAL
  *   stream           : hipStream_t (NULL = the default stream)
  */
 int ecoserve_kv_append(ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,
@@ -283,7 +287,7 @@ int ecoserve_attn_decode_append(ecoserve_ctx* ctx, const void* q, int64_t q_row_
                                 void* out, float* lse, int32_t B, int32_t max_ctx_len, void* stream);
 
 /*
- * Machine ceilings for the roofline reasoning of Section 2.2 (Table 2 prices
+ * Machine ceilings for the roofline reasoning of Section 2.1 (Table 2 prices
  * decode attention in bytes read, prefill attention in matrix FLOPs): what
  * `device` sustains on each resource, to be reported beside the published
  * peaks.  Measurement helpers, not hot calls: they allocate their own device

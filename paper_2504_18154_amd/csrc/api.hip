@@ -12,7 +12,7 @@
 
 using namespace eco;
 
-namespace {
+namespace eco {
 
 bool layout_ok(const ecoserve_layout* L, int* status) {
   *status = ECOSERVE_EINVAL;
@@ -30,6 +30,10 @@ bool layout_ok(const ecoserve_layout* L, int* status) {
   *status = ECOSERVE_OK;
   return true;
 }
+
+}  // namespace eco
+
+namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -50,45 +54,64 @@ int32_t plan_split_tokens(const ecoserve_ctx* c, int32_t B, int32_t max_ctx_len)
   return st;
 }
 
-int alloc_workspace(ecoserve_ctx* c, int32_t min_split_tokens) {
+// Partial-state slots (128 floats of ws_acc and 2 of ws_ml each) the context's current options can ask for.
+// Matrix-core decode: two groups of G per wavefront of the launch - the persistent grid, or the larger grid
+// of a forced split at the context's limits.  Plain decode: one per (sequence, query head, split).
+int64_t slots_needed(const ecoserve_ctx* c, int32_t* plain_splits) {
+  *plain_splits = 0;
+  if (use_mfma(c)) {
+    const int64_t waves = decode_mfma_waves(c->max_batch, c->lay.num_kv_heads, c->max_blocks_per_seq * kBlockSize,
+                                            c->opt_split_tokens, c->num_cu * kDecodeWgsPerCu);
+    return 2 * waves * (c->lay.num_q_heads / c->lay.num_kv_heads);
+  }
   // a sequence of n blocks cut into chunks of >= c blocks at arbitrary offsets has at most n/c + 2 pieces
-  const int32_t splits = ceil_div(c->max_blocks_per_seq * kBlockSize, min_split_tokens) + 2;
-  if (c->ws_acc && splits <= c->ws_splits) return ECOSERVE_OK;
-  if (c->ws_acc) (void)hipFree(c->ws_acc);
-  if (c->ws_ml) (void)hipFree(c->ws_ml);
-  if (c->ws_meta) (void)hipFree(c->ws_meta);
-  if (c->ws_plan) (void)hipFree(c->ws_plan);
+  *plain_splits = ceil_div(c->max_blocks_per_seq * kBlockSize, kMinSplitTokens) + 2;
+  return (int64_t)c->max_batch * c->lay.num_q_heads * *plain_splits;
+}
+
+// Makes the partial-state arrays large enough for the current options (they only ever grow).  Called where
+// allocation is allowed: ecoserve_create and ecoserve_set_option.
+int ensure_partial_states(ecoserve_ctx* c) {
+  int32_t plain_splits;
+  const int64_t need = slots_needed(c, &plain_splits);
+  if (plain_splits) c->ws_splits = plain_splits;
+  if (need <= c->ws_slots) return ECOSERVE_OK;
+  if (c->ws_acc || c->ws_ml) {
+    if (hipDeviceSynchronize() != hipSuccess) return ECOSERVE_EHIP;  // launches in flight may still use them
+    if (c->ws_acc) (void)hipFree(c->ws_acc);
+    if (c->ws_ml) (void)hipFree(c->ws_ml);
+    c->ws_bytes -= (size_t)c->ws_slots * (c->lay.head_dim + 2) * sizeof(float);
+  }
   c->ws_acc = nullptr;
   c->ws_ml = nullptr;
-  c->ws_meta = nullptr;
-  c->ws_plan = nullptr;
-  c->plan_key.valid = false;
-  c->ws_splits = 0;
-  c->ws_bytes = 0;
-  const size_t slots = (size_t)c->max_batch * c->lay.num_q_heads * splits;
-  const size_t acc_bytes = slots * c->lay.head_dim * sizeof(float);
-  const size_t ml_bytes = slots * 2 * sizeof(float);
-  if (slots == 0) return ECOSERVE_OK;
-  if (hipMalloc(&c->ws_acc, acc_bytes) != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_ENOMEM; }
+  c->ws_slots = 0;
+  const size_t acc_bytes = (size_t)need * c->lay.head_dim * sizeof(float);
+  const size_t ml_bytes = (size_t)need * 2 * sizeof(float);
+  if (hipMalloc(&c->ws_acc, acc_bytes) != hipSuccess || hipMalloc(&c->ws_ml, ml_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    if (c->ws_acc) (void)hipFree(c->ws_acc);
+    c->ws_acc = nullptr;
+    c->ws_ml = nullptr;
+    return ECOSERVE_ENOMEM;
+  }
+  c->ws_slots = need;
+  c->ws_bytes += acc_bytes + ml_bytes;
+  return ECOSERVE_OK;
+}
+
+// The parts of the workspace whose size the options do not change: the decode launch's numbering and the
+// prefill plan.
+int alloc_fixed_workspace(ecoserve_ctx* c) {
   const size_t meta_bytes = ((size_t)c->max_batch + 19) * sizeof(int32_t);
   // a prefill batch cannot bring more new tokens than the pool holds
   c->plan_tiles = prefill_plan_tiles(c->max_batch, (int32_t)std::min<int64_t>(
                                                         (int64_t)c->lay.num_blocks * kBlockSize, 0x7fffffffLL));
   const size_t plan_bytes = ((size_t)kPlanHeaderInts + (size_t)c->plan_tiles * kRecInts) * sizeof(int32_t);
-  if (hipMalloc(&c->ws_ml, ml_bytes) != hipSuccess || hipMalloc(&c->ws_meta, meta_bytes) != hipSuccess ||
-      hipMalloc(&c->ws_plan, plan_bytes) != hipSuccess) {
+  if (hipMalloc(&c->ws_meta, meta_bytes) != hipSuccess || hipMalloc(&c->ws_plan, plan_bytes) != hipSuccess) {
     (void)hipGetLastError();
-    (void)hipFree(c->ws_acc);
-    if (c->ws_ml) (void)hipFree(c->ws_ml);
-    if (c->ws_meta) (void)hipFree(c->ws_meta);
-    c->ws_acc = nullptr;
-    c->ws_ml = nullptr;
-    c->ws_meta = nullptr;
-    c->ws_plan = nullptr;
     return ECOSERVE_ENOMEM;
   }
-  c->ws_splits = splits;
-  c->ws_bytes = acc_bytes + ml_bytes + meta_bytes + plan_bytes;
+  c->ws_bytes += meta_bytes + plan_bytes;
   return ECOSERVE_OK;
 }
 
@@ -188,10 +211,13 @@ int ecoserve_create(ecoserve_ctx** out, int device, const ecoserve_layout* layou
   c->ws_plan = nullptr;
   c->plan_tiles = 0;
   c->ws_splits = 0;
+  c->ws_slots = 0;
   c->ws_bytes = 0;
   for (int i = 0; i < 3; ++i) c->ev_used[i] = 0, c->prof_seq[i] = 0;
-  st = alloc_workspace(c, kMinSplitTokens);
-  if (st != ECOSERVE_OK) { delete c; return st; }
+  st = alloc_fixed_workspace(c);
+  if (st == ECOSERVE_OK) st = ensure_partial_states(c);
+  if (st == ECOSERVE_OK && prepare_kv_append(c) != hipSuccess) st = ECOSERVE_EHIP;
+  if (st != ECOSERVE_OK) { (void)ecoserve_destroy(c); return st; }
   {
     // per-XCD shares start equal; samples of 4 wavefronts per CU follow, then each chunk's report to the merge
     const size_t share_bytes = (24 + 6 * (size_t)c->num_cu * kDecodeWgsPerCu * 4) * sizeof(int32_t);
@@ -227,13 +253,24 @@ int ecoserve_destroy(ecoserve_ctx* c) {
 int ecoserve_set_option(ecoserve_ctx* c, int32_t option, int32_t value) {
   if (!c) return ECOSERVE_EINVAL;
   switch (option) {
-    case ECOSERVE_OPT_DECODE_SPLIT_TOKENS:
+    case ECOSERVE_OPT_DECODE_SPLIT_TOKENS: {
       if (value != 0 && (value < kMinSplitTokens || value > kMaxSplitTokens || value % 64 != 0)) return ECOSERVE_EINVAL;
+      // a forced split launches a grid that grows with the batch, and so do its partial states
+      const int32_t before = c->opt_split_tokens;
       c->opt_split_tokens = value;
-      return ECOSERVE_OK;
-    case ECOSERVE_OPT_FORCE_PLAIN:
+      DeviceGuard guard(c->device);
+      const int st = guard.ok ? ensure_partial_states(c) : ECOSERVE_EHIP;
+      if (st != ECOSERVE_OK) c->opt_split_tokens = before;
+      return st;
+    }
+    case ECOSERVE_OPT_FORCE_PLAIN: {
+      const int32_t before = c->opt_force_plain;
       c->opt_force_plain = value ? 1 : 0;
-      return ECOSERVE_OK;
+      DeviceGuard guard(c->device);
+      const int st = guard.ok ? ensure_partial_states(c) : ECOSERVE_EHIP;
+      if (st != ECOSERVE_OK) c->opt_force_plain = before;
+      return st;
+    }
     case ECOSERVE_OPT_PROFILE:
       if (value < 0) return ECOSERVE_EINVAL;
       c->opt_profile = value;
@@ -273,7 +310,7 @@ int ecoserve_kv_append_strided(ecoserve_ctx* c, void* k_cache, void* v_cache, co
   if (!stride_ok(c, new_row_stride, c->lay.num_kv_heads)) return ECOSERVE_EINVAL;
   if (B == 0 || T == 0) return ECOSERVE_OK;
   if (!k_cache || !v_cache || !k_new || !v_new || !cu_q || !ctx_before || !block_table) return ECOSERVE_EINVAL;
-  if (B > c->max_batch || bt_stride <= 0 || max_new_len > T) return ECOSERVE_EINVAL;
+  if (B > c->max_batch || bt_stride <= 0 || max_new_len > T || max_new_len == 0) return ECOSERVE_EINVAL;
   if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_new) || !aligned16(v_new)) return ECOSERVE_EINVAL;
   DeviceGuard guard(c->device);
   if (!guard.ok) return ECOSERVE_EHIP;
@@ -341,6 +378,12 @@ int ecoserve_attn_prefill_strided(ecoserve_ctx* c, const void* q, int64_t q_row_
     const int32_t n_wgs = c->num_cu * kPrefillWgsPerCu;
     const int32_t grid = prefill_mfma_grid(a, T, n_wgs);
     auto& key = c->plan_key;
+    if (c->opt_reuse_plan) {
+      // whether a recorded launch builds the list or relies on an earlier one would be frozen into the graph
+      hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_EHIP; }
+      if (cap != hipStreamCaptureStatusNone) return ECOSERVE_EINVAL;
+    }
     const bool same = c->opt_reuse_plan && key.valid && key.cu_q == cu_q && key.ctx_before == ctx_before &&
                       key.block_table == block_table && key.bt_stride == bt_stride && key.B == B && key.T == T &&
                       key.n_wg == grid;
@@ -433,10 +476,10 @@ static int decode_impl(ecoserve_ctx* c, const void* q, int64_t q_row_stride, con
     {
       ProfileScope prof(c, ECOSERVE_KERNEL_DECODE, s);
       e = launch_decode_mfma(a, ctx_len, c->opt_split_tokens, max_ctx_len, n_wgs, c->ws_acc, c->ws_ml, c->ws_meta,
-                             c->ws_splits, share_in, share_out, speed, wave_samples, cuts, s);
+                             c->ws_slots / (2 * (a.Hq / a.Hkv)), share_in, share_out, speed, wave_samples, cuts, s);
     }
     if (e != hipSuccess) return ECOSERVE_EHIP;
-    e = launch_decode_mfma_merge(a, ctx_len, c->ws_acc, c->ws_ml, c->ws_meta, c->ws_splits, speed, wave_samples, cuts,
+    e = launch_decode_mfma_merge(a, ctx_len, c->ws_acc, c->ws_ml, c->ws_meta, speed, wave_samples, cuts,
                                  n_wgs * 4, s);
     return e == hipSuccess ? ECOSERVE_OK : ECOSERVE_EHIP;
   }

@@ -199,6 +199,16 @@ struct Chunking {
 };
 constexpr int kMetaPre = 18;  // ws_meta: [0..7] c, [8..16] cum, then the batch prefix sums
 
+// Where a cut piece's partial states live.  A chunk holds at most two cut pieces: its first piece, if the
+// (sequence, head) began in an earlier chunk (`begins` false), and its last piece, if the (sequence, head)
+// begins here and runs on into later chunks (`begins` true); a piece that is cut at both ends is the chunk's
+// only one.  So wavefront gw owns the two groups of G slots 2 gw and 2 gw + 1 (one slot per query head of the
+// group: 128 floats in ws_acc, 2 in ws_ml), and the workspace grows with the grid, not with the batch.
+// The k-th state of a (sequence, head) that begins in chunk w: group 2 w + 1 for k = 0, group 2 (w + k) after.
+__device__ __forceinline__ size_t partial_slot(int gw, bool begins, int G) {
+  return (size_t)(2 * gw + (begins ? 1 : 0)) * G;
+}
+
 template <int kDepth>
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const uint16_t* __restrict__ q, int q_row_stride, const uint16_t* __restrict__ k_new,
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
     const char* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, int bt_stride, const int32_t* __restrict__ ctx_len,
     uint16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
-    int32_t* __restrict__ ws_meta, int ws_splits, int c_forced, const float* __restrict__ share_in,
+    int32_t* __restrict__ ws_meta, int c_forced, const float* __restrict__ share_in,
     float* __restrict__ share_out, const float* __restrict__ xcd_speed, int32_t* __restrict__ ws_wave,
     int32_t* __restrict__ ws_cut, int B, int Hq, int Hkv, int G, float scale_log2e) {
   __shared__ int pre[kMaxBatch + 1];
@@ -553,9 +563,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
         ++n_buf;
       } else {  // a cut (sequence, head): at most the first and the last piece of a chunk
         if (col < G) {
-          const int h = cur.g * G + col;
-          const int split = gw - ch.owner(cur.seg_u0 + kPieceCost);  // counted from the chunk that holds block 0
-          const size_t slot = ((size_t)cur.b * Hq + h) * ws_splits + split;
+          const size_t slot = partial_slot(gw, cur.blk0 == 0, G) + col;
 #pragma unroll
           for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(ws_acc + slot * 128 + dt * 16 + 4 * quad) = acc[dt];
           if (quad == 0) {
@@ -648,12 +656,13 @@ __device__ __forceinline__ void append_new_tokens(const AppendJob& j, int bid, i
   }
 }
 
-// The n_split partial states of one (sequence, query head), slots base .. base + n_split - 1, into its
-// output row (and log-sum-exp); one wavefront, lanes own pairs of head-vector elements.
+// The n_split partial states of one query head (number i of its group) of a (sequence, K/V head) that begins
+// in chunk w, into its output row (and log-sum-exp); one wavefront, lanes own pairs of head-vector elements.
 __device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
-                                               size_t base, int n_split, uint16_t* __restrict__ orow,
+                                               int w, int i, int G, int n_split, uint16_t* __restrict__ orow,
                                                float* __restrict__ lse_out) {
   const int lane = threadIdx.x;
+  auto slot = [&](int k) { return partial_slot(w + k, k == 0, G) + i; };
   float M = -INFINITY;
   float lsum = 0.f, o0 = 0.f, o1 = 0.f;
   if (n_split <= 4) {
@@ -663,32 +672,32 @@ __device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc,
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const bool in = k < n_split;
-      mk[k] = in ? ws_ml[(base + k) * 2] : -INFINITY;
-      lk[k] = in ? ws_ml[(base + k) * 2 + 1] : 0.f;
-      ak[k] = in ? *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane) : float2{0.f, 0.f};
+      mk[k] = in ? ws_ml[slot(k) * 2] : -INFINITY;
+      lk[k] = in ? ws_ml[slot(k) * 2 + 1] : 0.f;
+      ak[k] = in ? *reinterpret_cast<const float2*>(ws_acc + slot(k) * 128 + 2 * lane) : float2{0.f, 0.f};
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) M = fmaxf(M, mk[k]);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const float w = k < n_split ? exp2f(mk[k] - M) : 0.f;
-      lsum += lk[k] * w;
-      o0 += ak[k].x * w;
-      o1 += ak[k].y * w;
+      const float wk = k < n_split ? exp2f(mk[k] - M) : 0.f;
+      lsum += lk[k] * wk;
+      o0 += ak[k].x * wk;
+      o1 += ak[k].y * wk;
     }
   } else {
-    for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[(base + k) * 2]);
+    for (int k = 0; k < n_split; ++k) M = fmaxf(M, ws_ml[slot(k) * 2]);
     for (int k = 0; k < n_split; ++k) {
-      const float w = exp2f(ws_ml[(base + k) * 2] - M);
-      lsum += ws_ml[(base + k) * 2 + 1] * w;
-      const float2 a = *reinterpret_cast<const float2*>(ws_acc + (base + k) * 128 + 2 * lane);
-      o0 += a.x * w;
-      o1 += a.y * w;
+      const float wk = exp2f(ws_ml[slot(k) * 2] - M);
+      lsum += ws_ml[slot(k) * 2 + 1] * wk;
+      const float2 a = *reinterpret_cast<const float2*>(ws_acc + slot(k) * 128 + 2 * lane);
+      o0 += a.x * wk;
+      o1 += a.y * wk;
     }
   }
   const float inv = 1.f / lsum;
-  const uint32_t w = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
-  *reinterpret_cast<uint32_t*>(orow + 2 * lane) = w;
+  const uint32_t packed = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
+  *reinterpret_cast<uint32_t*>(orow + 2 * lane) = packed;
   if (lse_out && lane == 0) *lse_out = (M + log2f(lsum)) * kLn2;
 }
 
@@ -697,7 +706,7 @@ __device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc,
 // grid (Hq, B), 64 threads; lanes own pairs of head-vector elements.
 __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __restrict__ ws_acc,
                                                               const float* __restrict__ ws_ml,
-                                                              const int32_t* __restrict__ ws_meta, int ws_splits,
+                                                              const int32_t* __restrict__ ws_meta,
                                                               uint16_t* __restrict__ out, float* __restrict__ lse,
                                                               float* __restrict__ xcd_speed,
                                                               const int32_t* __restrict__ ws_wave, int n_waves,
@@ -708,9 +717,10 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
   const Chunking ch = {ws_meta, ws_meta + 8};
   const int p0 = ws_meta[kMetaPre + b], nu = ws_meta[kMetaPre + b + 1] - p0;  // units: kPieceCost + blocks
   const long long seg_u0 = (long long)p0 * Hkv + (long long)g * nu;
-  const int n_split = ch.owner(seg_u0 + nu - 1) - ch.owner(seg_u0 + kPieceCost) + 1;
+  const int w0 = ch.owner(seg_u0 + kPieceCost);  // the chunk that holds block 0
+  const int n_split = ch.owner(seg_u0 + nu - 1) - w0 + 1;
   if (n_split <= 1) return;  // written in final form by the decode kernel
-  merge_partials(ws_acc, ws_ml, ((size_t)b * Hq + h) * ws_splits, n_split, out + ((size_t)b * Hq + h) * 128,
+  merge_partials(ws_acc, ws_ml, w0, h - g * G, G, n_split, out + ((size_t)b * Hq + h) * 128,
                  lse ? lse + (size_t)b * Hq + h : nullptr);
 }
 
@@ -720,7 +730,7 @@ __global__ __launch_bounds__(64) void decode_flat_merge_kernel(const float* __re
 // cuts, and this grid does not grow with it.
 __global__ __launch_bounds__(64) void decode_cut_merge_kernel(const float* __restrict__ ws_acc,
                                                              const float* __restrict__ ws_ml,
-                                                             const int32_t* __restrict__ ws_cut, int ws_splits,
+                                                             const int32_t* __restrict__ ws_cut,
                                                              uint16_t* __restrict__ out, float* __restrict__ lse,
                                                              float* __restrict__ xcd_speed,
                                                              const int32_t* __restrict__ ws_wave, int n_waves,
@@ -731,23 +741,31 @@ __global__ __launch_bounds__(64) void decode_cut_merge_kernel(const float* __res
   append_new_tokens(job, w * G + (int)blockIdx.y, (int)(gridDim.x * gridDim.y));
   if (xcd_speed && w * G + (int)blockIdx.y < 8) measure_xcd_speed(xcd_speed, ws_wave, n_waves, w * G + blockIdx.y);
   if (n_split <= 1) return;
-  merge_partials(ws_acc, ws_ml, ((size_t)b * Hq + h) * ws_splits, n_split, out + ((size_t)b * Hq + h) * 128,
+  merge_partials(ws_acc, ws_ml, w, (int)blockIdx.y, G, n_split, out + ((size_t)b * Hq + h) * 128,
                  lse ? lse + (size_t)b * Hq + h : nullptr);
+}
+
+int64_t decode_mfma_waves(int32_t B, int32_t Hkv, int32_t max_ctx_len, int32_t split_tokens,
+                          int32_t n_persistent_wgs) {
+  if (split_tokens <= 0) return (int64_t)n_persistent_wgs * kWaves;
+  // forced chunk size: the grid must cover the largest possible number of units
+  const int64_t c_forced = split_tokens / kBlockSize;
+  const int64_t u_max = (int64_t)B * Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize + kPieceCost);
+  const int64_t waves = (u_max + c_forced - 1) / c_forced;
+  return (waves + kWaves - 1) / kWaves * kWaves;
 }
 
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
                               int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta,
-                              int32_t ws_splits, const float* share_in, float* share_out, const float* xcd_speed,
+                              int64_t ws_waves, const float* share_in, float* share_out, const float* xcd_speed,
                               int32_t* ws_wave, int32_t* ws_cut, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  int n_wg = n_persistent_wgs;
+  const int64_t n_waves = decode_mfma_waves(a.B, a.Hkv, max_ctx_len, split_tokens, n_persistent_wgs);
+  if (n_waves > ws_waves || n_waves / kWaves > 0x7fffffffLL) return hipErrorInvalidValue;  // the workspace holds two slot groups per wavefront
+  const int n_wg = (int)(n_waves / kWaves);
   int c_forced = 0;
   if (split_tokens > 0) {
-    // forced chunk size: the grid must cover the largest possible number of units
     c_forced = split_tokens / kBlockSize;
-    const long long u_max = (long long)a.B * a.Hkv * ((max_ctx_len + kBlockSize - 1) / kBlockSize + kPieceCost);
-    const long long waves = (u_max + c_forced - 1) / c_forced;
-    n_wg = (int)((waves + kWaves - 1) / kWaves);
     share_in = nullptr;
     ws_cut = nullptr;  // sized for the persistent grid only
   }
@@ -756,7 +774,7 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
   auto launch = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_wg), dim3(kWaves * 64), 0, s, (const uint16_t*)a.q, a.q_row_stride,
                        (const uint16_t*)a.k_new, (const uint16_t*)a.v_new, a.new_row_stride, (const char*)a.k_cache, (const char*)a.v_cache, a.block_table, a.bt_stride, ctx_len,
-                       (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, ws_splits, c_forced, share_in, share_out,
+                       (uint16_t*)a.out, a.lse, ws_acc, ws_ml, ws_meta, c_forced, share_in, share_out,
                        xcd_speed, ws_wave, ws_cut, a.B, a.Hq, a.Hkv, G, a.scale_log2e);
   };
   launch(decode_mfma_kernel<kDecodeDepth>);
@@ -764,19 +782,19 @@ hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t
 }
 
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const int32_t* ctx_len, const float* ws_acc, const float* ws_ml,
-                                    const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
+                                    const int32_t* ws_meta, float* xcd_speed,
                                     const int32_t* ws_wave, const int32_t* ws_cut, int32_t n_waves, hipStream_t s) {
   const AppendJob job = {(const uint16_t*)a.k_new, (const uint16_t*)a.v_new, a.new_row_stride,
                          (uint16_t*)const_cast<void*>(a.k_cache), (uint16_t*)const_cast<void*>(a.v_cache),
                          a.block_table, a.bt_stride, ctx_len, a.B, a.Hkv};
   if (ws_cut) {
     hipLaunchKernelGGL(decode_cut_merge_kernel, dim3((unsigned)n_waves, (unsigned)(a.Hq / a.Hkv)), dim3(64), 0, s,
-                       ws_acc, ws_ml, ws_cut, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq,
+                       ws_acc, ws_ml, ws_cut, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq,
                        a.Hq / a.Hkv, job);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(decode_flat_merge_kernel, dim3((unsigned)a.Hq, (unsigned)a.B), dim3(64), 0, s, ws_acc, ws_ml,
-                     ws_meta, ws_splits, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq, a.Hkv,
+                     ws_meta, (uint16_t*)a.out, a.lse, xcd_speed, ws_wave, n_waves, a.Hq, a.Hkv,
                      a.Hq / a.Hkv, job);
   return hipGetLastError();
 }

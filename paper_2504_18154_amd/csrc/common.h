@@ -80,9 +80,12 @@ struct ecoserve_ctx {
   int32_t opt_profile;         // 0 off, n: time every n-th hot call of each kind
   int32_t opt_adaptive;        // decode: per-XCD shares of the stream follow measured speeds
   int32_t opt_reuse_plan;      // prefill: calls that name the same batch arrays share one tile list
-  // split-context workspace: unnormalised partial outputs and (max, sum) pairs
-  float* ws_acc;               // [max_batch][Hq][ws_splits][D]
-  float* ws_ml;                // [max_batch][Hq][ws_splits][2]
+  // split-context workspace: unnormalised partial outputs and (max, sum) pairs, ws_slots slots of D floats
+  // and of 2.  Matrix-core decode: two groups of G slots per wavefront of the launch; plain decode:
+  // [max_batch][Hq][ws_splits].
+  float* ws_acc;
+  float* ws_ml;
+  int64_t ws_slots;
   int32_t* ws_meta;            // [max_batch + 19]: chunk sizes and batch prefix sums of the last decode launch
   float* ws_share;             // per-XCD shares (mean 1) [2][8], speeds [8], then as int32 [2 * wavefronts]: units, ticks,
                                // then [4 * wavefronts]: the cut (sequence, K/V head) each chunk reports to the merge
@@ -124,7 +127,13 @@ struct AttnArgs {
   float scale_log2e;  // softmax scale times log2(e): scores live in the exp2 domain
 };
 
+// api.hip: *status = ECOSERVE_OK and true, or the status that names what is wrong with the layout
+bool layout_ok(const ecoserve_layout* L, int* status);
+
 // kv_append.hip
+// (at context creation: a batch of thousands needs more dynamic LDS than a kernel may use by default, and the
+// limit is raised here, once, rather than by a hot call)
+hipError_t prepare_kv_append(const ecoserve_ctx* ctx);
 // (new_row_stride: elements between the K rows, and between the V rows, of consecutive tokens.  With
 // max_new_len <= 1, cu_q may be NULL: one token per sequence, token b for sequence b, stored at position
 // ctx_before[b] + pos_bias; otherwise pos_bias must be 0.)
@@ -146,14 +155,18 @@ hipError_t launch_decode_merge(const AttnArgs& a, const int32_t* ctx_len, int32_
 // (split_tokens 0 = equal share per wavefront of the persistent grid; > 0 forces the chunk size)
 // (share_in / share_out: per-XCD shares [8] read and left for the next launch; xcd_speed [8]: speeds the merge
 // kernel measured from the per-wavefront samples ws_wave [2 * wavefronts]; share_in NULL: equal chunks)
+// (partial states: two groups of G slots per wavefront of the launch, so ws_acc holds 2 * ws_waves * G * 128
+// floats and ws_ml 2 * ws_waves * G * 2; decode_mfma_waves() says how many wavefronts a launch has; a launch
+// that needs more than ws_waves is refused with hipErrorInvalidValue)
+int64_t decode_mfma_waves(int32_t B, int32_t Hkv, int32_t max_ctx_len, int32_t split_tokens, int32_t n_persistent_wgs);
 hipError_t launch_decode_mfma(const AttnArgs& a, const int32_t* ctx_len, int32_t split_tokens, int32_t max_ctx_len,
-                              int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta, int32_t ws_splits,
+                              int32_t n_persistent_wgs, float* ws_acc, float* ws_ml, int32_t* ws_meta, int64_t ws_waves,
                               const float* share_in, float* share_out, const float* xcd_speed, int32_t* ws_wave,
                               int32_t* ws_cut, hipStream_t s);
 // (with a.k_new given, the merge launch also stores every sequence's new token into the cache, position
 // ctx_len[b] - 1: the decode kernel has taken it from the new rows and left the cache alone)
 hipError_t launch_decode_mfma_merge(const AttnArgs& a, const int32_t* ctx_len, const float* ws_acc, const float* ws_ml,
-                                    const int32_t* ws_meta, int32_t ws_splits, float* xcd_speed,
+                                    const int32_t* ws_meta, float* xcd_speed,
                                     const int32_t* ws_wave, const int32_t* ws_cut, int32_t n_waves, hipStream_t s);
 
 // attn_prefill_mfma.hip: bf16, D = 128

@@ -196,11 +196,8 @@ static void launch_tiled(const ecoserve_layout& L, void* k_cache, void* v_cache,
   // a sequence with S new tokens touches at most S/16 + 2 blocks (ragged at both ends), and none if S == 0
   const int64_t max_units = (int64_t)T / 16 + 2 * (int64_t)(B < T ? B : T);
   const dim3 grid((unsigned)max_units, (unsigned)(L.num_kv_heads / HPW));
+  // (above 64 KiB - a batch of thousands - the kernel's limit was raised when the context was created)
   const size_t lds = append_lds_bytes<E>(B, L.head_dim, HPW);
-  // more than 64 KiB of LDS needs the kernel's limit raised (a batch of thousands; rare, so not cached)
-  if (lds > 60 * 1024)
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&kv_append_kernel<E, HPW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL((kv_append_kernel<E, HPW>), grid, dim3(kAppendThreads), lds, s, (E*)k_cache, (E*)v_cache,
                      (const E*)k_new, (const E*)v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B,
                      L.num_kv_heads, L.head_dim);
@@ -224,6 +221,23 @@ static void launch_typed(const ecoserve_layout& L, void* k_cache, void* v_cache,
   } else {
     launch_tiled<E, 1>(L, k_cache, v_cache, k_new, v_new, new_row_stride, cu_q, ctx_before, block_table, bt_stride, B, T, s);
   }
+}
+
+template <typename E, int HPW>
+static hipError_t raise_lds_limit(const ecoserve_ctx* ctx) {
+  const size_t lds = append_lds_bytes<E>(ctx->max_batch, ctx->lay.head_dim, HPW);
+  if (lds <= 60 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&kv_append_kernel<E, HPW>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
+hipError_t prepare_kv_append(const ecoserve_ctx* ctx) {
+  const int hkv = ctx->lay.num_kv_heads;
+  if (ctx->lay.dtype == ECOSERVE_BF16)
+    return hkv % 4 == 0 ? raise_lds_limit<uint16_t, 4>(ctx) : hkv % 2 == 0 ? raise_lds_limit<uint16_t, 2>(ctx)
+                                                                          : raise_lds_limit<uint16_t, 1>(ctx);
+  return hkv % 4 == 0 ? raise_lds_limit<float, 4>(ctx) : hkv % 2 == 0 ? raise_lds_limit<float, 2>(ctx)
+                                                                      : raise_lds_limit<float, 1>(ctx);
 }
 
 hipError_t launch_kv_append(const ecoserve_ctx* ctx, void* k_cache, void* v_cache, const void* k_new,

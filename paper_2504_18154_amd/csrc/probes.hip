@@ -1,5 +1,5 @@
 // Machine ceilings: what this GPU sustains on the two resources the paper's roofline
-// argument (Section 2.2, Table 2) prices attention against -- bytes read from device memory
+// argument (Section 2.1, Table 2) prices attention against -- bytes read from device memory
 // (the decode phase) and bf16 matrix-core FLOPs (the prefill phase).  The published peaks are
 // the denominators of every reported fraction; these two short measurements say how much of
 // each peak any kernel could reach on the device at hand, so a reader can tell a kernel's
