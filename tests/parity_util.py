@@ -14,10 +14,20 @@ from paper_2504_18154_amd import workloads as wl
 # bar.  fp32: derived from fp32 accumulation over a few hundred keys plus exp2 error,
 # with two orders of magnitude of headroom.
 TOL = {"bf16": (1e-2, 1e-3), "f32": (1e-4, 1e-5)}
-# log-sum-exp (natural log).  The prefill kernel sums the bf16-rounded weights (the same
-# values the second product consumes), so the row sum carries a relative error of at most
-# half a bf16 spacing, 2^-9 = 1.95e-3, which is also the bound on the error of its log.
-LSE_TOL = {"bf16": 2.5e-3, "f32": 1e-4}
+# log-sum-exp (natural log): 1e-3 where the row sum is taken in fp32 (decode, the plain
+# kernels).  The matrix-core prefill kernel sums the bf16-rounded weights (the same values
+# the second product consumes, so numerator and denominator of the output agree).  A bf16
+# number has 8 significant bits: rounding to nearest moves a weight by at most half a
+# spacing, which relative to a value just above a power of two is 2^-8 = 3.9e-3.  With a
+# flat softmax the roundings of hundreds of weights average out (errors of 1e-4 in the
+# tests); with near one-hot weights the row sum is one weight and carries its full rounding
+# error, so 2^-8 is the bound on the relative error of the sum and hence on the error of its
+# log: 4e-3 there (`bf16_row_sum=True`) and nowhere else.
+LSE_TOL = {"bf16": 1e-3, "f32": 1e-4}
+LSE_TOL_BF16_ROW_SUM = 4e-3
+# Full-size workloads: at most this share of the output elements may miss the stated 1e-2
+# and rely on the bound for coarse bf16 outputs (see compare).
+MAX_RELAXED_SHARE = 1e-4
 
 
 def say(msg: str):
@@ -99,14 +109,17 @@ def bf16_ulp(x: np.ndarray) -> np.ndarray:
     return 2.0 ** (np.floor(np.log2(ax)) - 7)
 
 
-def compare(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None):
+def compare(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None, max_relaxed_share=None):
     """max-abs and mean-abs error of GPU output vs the fp64 oracle.
 
     bf16 outputs: the stated bounds are 1e-2 max-abs and 1e-3 mean-abs.  A bf16 number
-    with |o| >= 2 has spacing >= 2^-6 > 1e-2, so there the nearest representable value can
-    already miss the exact one by up to 0.0078 (|o| < 4) or 0.0156 (|o| < 8); such elements
-    (a handful: short contexts, where the output is close to a single large V entry) are
-    held to one bf16 spacing of the exact value instead.  Their count is printed."""
+    with |o| >= 2 has spacing >= 2^-6 > 1e-2, so rounding the exact result to the output type
+    alone can miss it by half a spacing (0.0078 for |o| < 4, 0.0156 for |o| < 8), and the
+    bf16 rounding of the weights before the second product adds up to 2^-9 |o|.  Elements
+    with |o| >= 2 (short contexts, where the output is close to a single large V entry) are
+    therefore held to max(1e-2, half a spacing + 2^-9 |o|); everything else to 1e-2.  The
+    number of elements that actually miss 1e-2 is printed and, with `max_relaxed_share`
+    (the full-size workloads), bounded as a share of all elements."""
     if rows is not None:   # select on the device first: full outputs can be gigabytes
         got = got[torch.as_tensor(np.asarray(rows), dtype=torch.long, device=got.device)]
     g = got.detach().double().cpu().numpy()
@@ -116,21 +129,29 @@ def compare(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None):
     mx, mean = float(err.max()) if err.size else 0.0, float(err.mean()) if err.size else 0.0
     tmax, tmean = TOL[dtype]
     bound = np.full(ref.shape, tmax)
-    coarse = 0
+    coarse = relaxed = 0
     if dtype == "bf16":
-        bound = np.maximum(bound, bf16_ulp(ref))
-        coarse = int((np.abs(ref) >= 2.0).sum())
+        big = np.abs(ref) >= 2.0
+        bound = np.where(big, np.maximum(tmax, 0.5 * bf16_ulp(ref) + 2.0 ** -9 * np.abs(ref)), tmax)
+        coarse = int(big.sum())
+        relaxed = int((err > tmax).sum())
     worst = float((err / bound).max()) if err.size else 0.0
-    say(f"  {name}: max-abs {mx:.3e} (<= {tmax:g}; {coarse} of {ref.size} elements with |o| >= 2 held to one "
-        f"bf16 spacing; worst err/bound {worst:.2f})  mean-abs {mean:.3e} (<= {tmean:g})")
+    say(f"  {name}: max-abs {mx:.3e} (<= {tmax:g}; {coarse} of {ref.size} elements have |o| >= 2, {relaxed} miss "
+        f"{tmax:g} and are held to half a bf16 spacing + 2^-9 |o|; worst err/bound {worst:.2f})  "
+        f"mean-abs {mean:.3e} (<= {tmean:g})")
     assert np.all(err <= bound) and mean <= tmean, f"{name}: max-abs {mx:.3e}, mean-abs {mean:.3e}, worst {worst:.2f}"
+    if max_relaxed_share is not None:
+        assert relaxed <= max_relaxed_share * ref.size, \
+            f"{name}: {relaxed} of {ref.size} elements miss {tmax:g} (more than a share of {max_relaxed_share:g})"
     return mx, mean
 
 
-def compare_lse(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None):
+def compare_lse(name, got: torch.Tensor, ref: np.ndarray, dtype: str, rows=None, bf16_row_sum=False):
+    """`bf16_row_sum`: the result comes from the matrix-core prefill kernel (see LSE_TOL)."""
     if rows is not None:
         got = got[torch.as_tensor(np.asarray(rows), dtype=torch.long, device=got.device)]
     g = got.detach().double().cpu().numpy()
+    tol = LSE_TOL_BF16_ROW_SUM if bf16_row_sum and dtype == "bf16" else LSE_TOL[dtype]
     err = float(np.abs(g - ref).max()) if ref.size else 0.0
-    say(f"  {name}: lse max-abs {err:.3e} (<= {LSE_TOL[dtype]:g})")
-    assert err <= LSE_TOL[dtype], f"{name}: lse error {err:.3e}"
+    say(f"  {name}: lse max-abs {err:.3e} (<= {tol:g})")
+    assert err <= tol, f"{name}: lse error {err:.3e}"

@@ -1,15 +1,18 @@
-"""GPU parity at the full sizes of the benchmark workloads (one layer each, in the launch
-configuration bench.py times): the 30B- and 70B-scale decode batches in full, the prefill
-batches on sampled query rows the oracle computes one by one, and the 70B temporal-
-disaggregation switch (resident decode batch, prefill burst into the same pool, decode steps
-with the union).  Caches are compared bit for bit over the whole pool after every append."""
+"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration
+bench.py times: the 30B- and 70B-scale decode batches in full on three layer caches with
+data of their own, the prefill batches on sampled query rows the oracle computes one by
+one, and the 70B temporal-disaggregation switch (resident decode batch, prefill burst
+into the same pool, then all 64 decode steps with the union, one layer).  Caches are
+compared bit for bit over the whole pool after every append.  At these sizes the share
+of output elements that miss the stated 1e-2 (coarse bf16 outputs, see
+parity_util.compare) is bounded, not only printed."""
 import numpy as np
 import pytest
 import torch
 
 from oracle import oracle as orc
 from paper_2504_18154_amd import binding, workloads as wl
-from tests.parity_util import Layer, compare, compare_lse, dev_i32, say
+from tests.parity_util import MAX_RELAXED_SHARE, Layer, compare, compare_lse, dev_i32, say
 
 pytestmark = pytest.mark.gpu
 
@@ -34,17 +37,24 @@ def _sample_rows(rng, q_len, extra=32):
     return np.asarray(start, np.int32), np.asarray(tok, np.int32), np.asarray(pos, np.int32)
 
 
-def _decode_full(db: wl.DecodeBatch, name):
+def _decode_full(db: wl.DecodeBatch, name, layers=1):
+    """`layers` caches one after the other, each with K, V and queries of its own (the layers of a model
+    differ in data only): every step below on each of them."""
+    for l in range(layers):
+        _decode_full_layer(db, f"{name}, layer cache {l}" if layers > 1 else name, 100 * l)
+
+
+def _decode_full_layer(db: wl.DecodeBatch, name, seed_offset):
     model = db.model
     say(f"{name}: B={db.B}, {int(db.ctx_len.sum())} cached tokens, pool {db.num_blocks} blocks")
     layer = Layer(model, db.num_blocks, db.B, db.block_table.shape[1])
-    k, v = _stream(model, int(db.ctx_len.sum()), db.seed + 1)
+    k, v = _stream(model, int(db.ctx_len.sum()), db.seed + 1 + seed_offset)
     layer.append(k, v, wl.cu_from_lengths(db.ctx_len), np.zeros(db.B, np.int32), db.block_table)
     layer.assert_cache_bit_exact()
-    q = wl.randn((db.B, model.Hq, model.D), model.dtype, db.seed + 3, device="cuda")
+    q = wl.randn((db.B, model.Hq, model.D), model.dtype, db.seed + 3 + seed_offset, device="cuda")
     out, lse = layer.decode_gpu(q, db.block_table, db.ctx_len)
     ref, ref_lse = layer.decode_oracle(q, db.block_table, db.ctx_len)
-    compare(f"{name} decode", out, ref, "bf16")
+    compare(f"{name} decode", out, ref, "bf16", max_relaxed_share=MAX_RELAXED_SHARE)
     compare_lse(f"{name} decode", lse, ref_lse, "bf16")
     out2, _ = layer.decode_gpu(q, db.block_table, db.ctx_len)
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "not run-to-run deterministic"
@@ -53,7 +63,7 @@ def _decode_full(db: wl.DecodeBatch, name):
     layer.ctx.set_option(binding.OPT_DECODE_ADAPTIVE, 1)
     for call in range(6):
         out, lse = layer.decode_gpu(q, db.block_table, db.ctx_len)
-        compare(f"{name} decode, adaptive shares, call {call}", out, ref, "bf16")
+        compare(f"{name} decode, adaptive shares, call {call}", out, ref, "bf16", max_relaxed_share=MAX_RELAXED_SHARE)
         compare_lse(f"{name} decode, adaptive shares, call {call}", lse, ref_lse, "bf16")
     # ... and the call bench.py times: the step's append fused into the decode call.  The last token of
     # every sequence is wiped from the cache (NaN bits) and handed in as the step's new token: the output
@@ -69,18 +79,18 @@ def _decode_full(db: wl.DecodeBatch, name):
         out = torch.full_like(q, float("nan"))
         lse = torch.full((db.B, model.Hq), float("nan"), dtype=torch.float32, device="cuda")
         layer.ctx.attn_decode_append(q, kn, vn, layer.kc, layer.vc, table, ctx_dev, out, db.max_ctx_len, lse)
-        compare(f"{name} fused append + decode, call {call}", out, ref, "bf16")
+        compare(f"{name} fused append + decode, call {call}", out, ref, "bf16", max_relaxed_share=MAX_RELAXED_SHARE)
         compare_lse(f"{name} fused append + decode, call {call}", lse, ref_lse, "bf16")
         layer.assert_cache_bit_exact()
     layer.close()
 
 
-def test_config2_decode_30b_one_layer_full():
-    _decode_full(wl.config2_decode_30b(), "config index 1 (30B decode)")
+def test_config2_decode_30b_three_layers_full():
+    _decode_full(wl.config2_decode_30b(), "config index 1 (30B decode)", layers=3)
 
 
-def test_config4_decode_70b_one_layer_full():
-    _decode_full(wl.config4_decode_70b(), "config index 3 (70B decode)")
+def test_config4_decode_70b_three_layers_full():
+    _decode_full(wl.config4_decode_70b(), "config index 3 (70B decode)", layers=3)
 
 
 def test_config3_prefill_30b_one_layer_sampled_rows():
@@ -95,8 +105,8 @@ def test_config3_prefill_30b_one_layer_sampled_rows():
     out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table, max_q_len=pb.max_q_len)
     start, tok, pos = _sample_rows(wl.rng_for(1), pb.q_len)
     ref, ref_lse = orc.attn_rows(layer.shape, wl.to_bits(q), layer.okc, layer.ovc, pb.block_table, start, tok, pos)
-    compare("prefill (sampled rows)", out, ref, "bf16", rows=tok)
-    compare_lse("prefill (sampled rows)", lse, ref_lse, "bf16", rows=tok)
+    compare("prefill (sampled rows)", out, ref, "bf16", rows=tok, max_relaxed_share=MAX_RELAXED_SHARE)
+    compare_lse("prefill (sampled rows)", lse, ref_lse, "bf16", rows=tok, bf16_row_sum=True)
     layer.close()
 
 
@@ -118,7 +128,7 @@ def test_chat_shaped_prefill_and_decode_batches_in_full(dataset, seed, n_prefill
     out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table, max_q_len=pb.max_q_len)
     ref, ref_lse = layer.prefill_oracle(q, pb.cu_q, pb.ctx_before, pb.block_table)
     compare(f"{dataset}-shaped prefill", out, ref, "bf16")
-    compare_lse(f"{dataset}-shaped prefill", lse, ref_lse, "bf16")
+    compare_lse(f"{dataset}-shaped prefill", lse, ref_lse, "bf16", bf16_row_sum=True)
     layer.close()
     _decode_full(wl.table4_decode_batch(model, dataset, n_decode, decode_seed), f"{dataset}-shaped decode batch")
 
@@ -146,19 +156,30 @@ def test_config5_switch_70b_one_layer():
     out, lse = layer.prefill_gpu(q, cu, zeros, table[nres:], max_q_len=int(q_len.max()))
     start, tok, pos = _sample_rows(wl.rng_for(2), q_len)
     ref, ref_lse = orc.attn_rows(layer.shape, wl.to_bits(q), layer.okc, layer.ovc, table[nres:], start, tok, pos)
-    compare("burst prefill (sampled rows)", out, ref, "bf16", rows=tok)
-    compare_lse("burst prefill (sampled rows)", lse, ref_lse, "bf16", rows=tok)
-    # decode-only steps with all 200 sequences
+    compare("burst prefill (sampled rows)", out, ref, "bf16", rows=tok, max_relaxed_share=MAX_RELAXED_SHARE)
+    compare_lse("burst prefill (sampled rows)", lse, ref_lse, "bf16", rows=tok, bf16_row_sum=True)
+    # decode-only phase: all 64 steps with all 200 sequences, alternately as two calls (append, then decode)
+    # and as the one fused call bench.py times; the cache is compared after every eighth step and at the end
     ctx = np.concatenate([resident, q_len]).astype(np.int32)
     ones = wl.cu_from_lengths([1] * B)
-    for step in range(3):
+    table_dev = dev_i32(table)
+    for step in range(64):
         kn, vn = _stream(model, B, 600 + 10 * step)
         qd = wl.randn((B, model.Hq, model.D), "bf16", 605 + 10 * step, device="cuda")
-        layer.append(kn, vn, ones, ctx, table, max_new_len=1)
-        ctx = ctx + 1
-        out, lse = layer.decode_gpu(qd, table, ctx)
+        if step % 2 == 0:
+            layer.append(kn, vn, ones, ctx, table, max_new_len=1)
+            ctx = ctx + 1
+            out, lse = layer.decode_gpu(qd, table, ctx)
+        else:
+            orc.kv_append(layer.shape, layer.okc, layer.ovc, wl.to_bits(kn), wl.to_bits(vn), ones, ctx, table)
+            ctx = ctx + 1
+            out = torch.full_like(qd, float("nan"))
+            lse = torch.full((B, model.Hq), float("nan"), dtype=torch.float32, device="cuda")
+            layer.ctx.attn_decode_append(qd, kn, vn, layer.kc, layer.vc, table_dev, dev_i32(ctx), out, int(ctx.max()), lse)
         ref, ref_lse = layer.decode_oracle(qd, table, ctx)
-        compare(f"decode step {step}", out, ref, "bf16")
+        compare(f"decode step {step}", out, ref, "bf16", max_relaxed_share=MAX_RELAXED_SHARE)
         compare_lse(f"decode step {step}", lse, ref_lse, "bf16")
+        if step % 8 == 7:
+            layer.assert_cache_bit_exact()
     layer.assert_cache_bit_exact()
     layer.close()
