@@ -287,6 +287,38 @@ int ecoserve_attn_decode_append(ecoserve_ctx* ctx, const void* q, int64_t q_row_
                                 void* out, float* lse, int32_t B, int32_t max_ctx_len, void* stream);
 
 /*
+ * ecoserve_attn_decode for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  No context: the layout is passed directly, and the scratch
+ * memory of the two launches (partial softmax states of the split contexts,
+ * the launch's numbering, the list of cut sequences) is a fixed array of
+ * 16.3 MiB inside the library's device code, one copy per GPU, held until the
+ * process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * events), does not synchronise, and launches the same kernels as
+ * ecoserve_attn_decode with its default options (persistent grid, equal
+ * shares), so the results are the same bits.
+ *
+ *   device      : ordinal of the GPU that holds every buffer (0 .. 63)
+ *   layout      : host; dtype BF16 with head_dim 128 only (the matrix-core
+ *                 kernels), else ECOSERVE_EUNSUPPORTED
+ *   q, k_cache, v_cache, block_table, bt_stride, ctx_len, out, lse,
+ *   max_ctx_len, stream : as in ecoserve_attn_decode (q and out packed
+ *                 [B][Hq][D]); max_ctx_len <= bt_stride * block_size
+ *   B           : at most 4096, else ECOSERVE_EINVAL (the array is sized for
+ *                 that batch, any group size up to 16 and a grid of up to 256
+ *                 workgroups; nothing else about the inputs is limited)
+ *
+ * All calls on one GPU share that GPU's array: calls that overlap there (two
+ * streams, two threads) race; order them.  The array needs no clearing
+ * between calls (a launch writes every word it later reads), and a call may
+ * follow a larger one.
+ */
+int ecoserve_attn_decode_noalloc(int device, const ecoserve_layout* layout, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* block_table, int32_t bt_stride,
+                                 const int32_t* ctx_len, void* out, float* lse, int32_t B, int32_t max_ctx_len,
+                                 void* stream);
+
+/*
  * Machine ceilings for the roofline reasoning of Section 2.1 (Table 2 prices
  * decode attention in bytes read, prefill attention in matrix FLOPs): what
  * `device` sustains on each resource, to be reported beside the published

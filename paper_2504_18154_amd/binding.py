@@ -27,7 +27,7 @@ EXPORTS = [
     "ecoserve_attn_prefill", "ecoserve_attn_decode", "ecoserve_debug_validate", "ecoserve_profile_read",
     "ecoserve_profile_reset", "ecoserve_probe_hbm_read", "ecoserve_probe_mfma_bf16",
     "ecoserve_kv_append_strided", "ecoserve_attn_prefill_strided", "ecoserve_attn_decode_strided",
-    "ecoserve_attn_decode_append",
+    "ecoserve_attn_decode_append", "ecoserve_attn_decode_noalloc",
 ]
 
 
@@ -69,6 +69,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.ecoserve_attn_prefill_strided.argtypes = [vp, vp, i64, vp, vp, i32p, i32p, i32p, i32, vp, vp, i32, i32, i32, vp]
     lib.ecoserve_attn_decode_strided.argtypes = [vp, vp, i64, vp, vp, i32p, i32, i32p, vp, vp, i32, i32, vp]
     lib.ecoserve_attn_decode_append.argtypes = [vp, vp, i64, vp, vp, i64, vp, vp, i32p, i32, i32p, vp, vp, i32, i32, vp]
+    lib.ecoserve_attn_decode_noalloc.argtypes = [ctypes.c_int, ctypes.POINTER(Layout), vp, vp, vp, i32p, i32, i32p, vp, vp,
+                                                 i32, i32, vp]
     lib.ecoserve_debug_validate.argtypes = [vp, i32p, i32p, i32p, i32, i32]
     lib.ecoserve_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ecoserve_profile_reset.argtypes = [vp]
@@ -124,6 +126,15 @@ def probe_mfma_bf16(random_operands: bool, reps: int = 5, device: int = 0) -> fl
 
 def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def attn_decode_noalloc(layout: Layout, q, k_cache, v_cache, block_table, ctx_len, out, max_ctx_len, lse=None,
+                        device: int = 0) -> int:
+    """ecoserve_attn_decode without a context and without any allocation; returns the status code."""
+    return int(_lib.ecoserve_attn_decode_noalloc(int(device), ctypes.byref(layout), _ptr(q), _ptr(k_cache),
+                                                 _ptr(v_cache), _ptr(block_table), int(block_table.shape[1]),
+                                                 _ptr(ctx_len), _ptr(out), _ptr(lse), int(ctx_len.numel()),
+                                                 int(max_ctx_len), _stream()))
 
 
 def _row_stride(t) -> int:

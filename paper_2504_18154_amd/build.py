@@ -17,7 +17,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libecoserve.so")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 
-SOURCES = ["api.hip", "kv_append.hip", "attn_plain.hip", "attn_decode_mfma.hip", "attn_prefill_mfma.hip", "probes.hip", "padg.hip"]
+SOURCES = ["api.hip", "kv_append.hip", "attn_plain.hip", "attn_decode_mfma.hip", "decode_noalloc.hip", "attn_prefill_mfma.hip", "probes.hip", "padg.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
          # packed fp32 VALU forms are kept out of generated code on this target
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
