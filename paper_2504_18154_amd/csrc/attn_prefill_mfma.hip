@@ -185,9 +185,16 @@ __device__ __forceinline__ void exp_tile(const f32x16& s, bf16x8 (&pf)[2], float
 // serve many launches without being rebuilt), then from kPlanHeaderInts one record of kRecInts per
 // query tile:
 //   0 sequence, 1 tile inside the sequence, 2 first packed token of the sequence, 3 S,
-//   4 ctx_before, 5 number of 64-key steps, 8..19 physical ids of the sequence's first 12 blocks
+//   4 ctx_before, 5 number of 64-key steps, 6 the tile's first query row, 7 the row behind its last,
+//   8..19 physical ids of the sequence's first 12 blocks
 // (clamped to its last block), i.e. everything a workgroup needs to start on the tile with one
-// load.  Records are sorted by the number of key steps, largest first, with a counting sort
+// load.
+// Where a prompt's tiles begin: a prompt of S = 128 n + r new tokens (0 < r < 128) has one ragged tile of r
+// rows.  As the last tile it would cost as many key steps as a full one (its rows see the whole prompt);
+// as the first tile it costs one or two.  Moving it to the front shifts the other tiles by r rows, which
+// costs each of them ceil((ctx_before + r) / 64) - ceil(ctx_before / 64) steps more: without a cached
+// prefix that is at most as many as the two steps saved per tile, and fewer when r <= 64.  tile_rows()
+// takes whichever alignment has fewer key steps in total.  Records are sorted by the number of key steps, largest first, with a counting sort
 // (tiles with kPlanBins - 1 or more steps share a class; the order inside a class is arbitrary).
 __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_t* __restrict__ cu_q,
                                                                     const int32_t* __restrict__ ctx_before,
@@ -218,6 +225,18 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     return run;
   };
   auto tiles_of = [&](int b) { return (cu_q[b + 1] - cu_q[b] + kTQ - 1) / kTQ; };
+  // rows [first, last) of tile qt of a prompt of S new tokens behind cb cached ones
+  auto tile_rows = [&](int S, long long cb, int qt, int& first, int& last) {
+    const int r = S % kTQ;
+    const long long up = (cb + r + kTK - 1) / kTK - (cb + kTK - 1) / kTK;  // steps each full tile gains if shifted by r
+    if (r > 0 && up < 2) {  // ragged tile first
+      first = qt == 0 ? 0 : r + (qt - 1) * kTQ;
+      last = qt == 0 ? r : first + kTQ;
+    } else {
+      first = qt * kTQ;
+      last = min(S, first + kTQ);
+    }
+  };
 
   const int per = (B + kPlanThreads - 1) / kPlanThreads, b0 = tid * per;
   int local = 0;
@@ -251,7 +270,9 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     b = lo;
     qt = i - pre[b];
     const int S = cu_q[b + 1] - cu_q[b];
-    const long long kv_end = (long long)ctx_before[b] + (long long)qt * kTQ + min(kTQ, S - qt * kTQ);
+    int first, last;
+    tile_rows(S, ctx_before[b], qt, first, last);
+    const long long kv_end = (long long)ctx_before[b] + last;
     steps = (int)((kv_end + kTK - 1) / kTK);
     const int cls = kPlanBins - 1 - min(steps, kPlanBins - 1);  // class 0 = heaviest
     return S <= P ? kPlanBins + cls : cls;
@@ -295,8 +316,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
     rec[3] = S;
     rec[4] = cb;
     rec[5] = steps;
-    rec[6] = 0;
-    rec[7] = 0;
+    tile_rows(S, cb, qt, rec[6], rec[7]);
     for (int j = 0; j < 12; ++j) rec[8 + j] = block_table[(size_t)b * bt_stride + min(j, nblk_total - 1)];
   }
   if (tid == 0) plan[0] = n_tiles_all;
@@ -308,7 +328,7 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(const int32_
 // Wave-uniform description of one work item (a query tile of one query head).
 constexpr int kPackedItem = 1 << 30;  // flag in the query head number handed to describe(): a packed tile
 struct Item {
-  int tok0, S, cb, q0, g, h, n_tiles;
+  int tok0, S, cb, q0, q_end, g, h, n_tiles;  // q0, q_end: the tile's query rows [q0, q_end) of the prompt's S
   bool pk;  // packed tile: rows are (query head h + row / P, position row % P)
   const int32_t* bt_row;
   __device__ __forceinline__ int L_total() const { return cb + S; }
@@ -319,7 +339,7 @@ struct Item {
 __device__ __forceinline__ Item describe(int rec, int g, int h, const int32_t* __restrict__ block_table,
                                          int bt_stride) {
   Item t;
-  const int b = __builtin_amdgcn_readlane(rec, 0), qt = __builtin_amdgcn_readlane(rec, 1);
+  const int b = __builtin_amdgcn_readlane(rec, 0);
   t.tok0 = __builtin_amdgcn_readlane(rec, 2);
   t.S = __builtin_amdgcn_readlane(rec, 3);
   t.cb = __builtin_amdgcn_readlane(rec, 4);
@@ -327,7 +347,8 @@ __device__ __forceinline__ Item describe(int rec, int g, int h, const int32_t* _
   t.g = g;
   t.h = h & (kPackedItem - 1);
   t.pk = (h & kPackedItem) != 0;
-  t.q0 = qt * kTQ;
+  t.q0 = __builtin_amdgcn_readlane(rec, 6);
+  t.q_end = __builtin_amdgcn_readlane(rec, 7);
   t.bt_row = block_table + (size_t)b * bt_stride;
   return t;
 }
@@ -429,7 +450,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     } else {
       hq = 0;
       r = t.q0 + rr;
-      ok = r < t.S;
+      ok = r < t.q_end;
     }
   };
   auto enter = [&](const Item& t) {
@@ -439,8 +460,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     pos = t.cb + row;                                      // absolute position = causal bound
     // smallest / largest bound in this wavefront (packed: of the tile, every wavefront sees every position)
     w_pmin = kMayPack && t.pk ? t.cb : t.cb + t.q0 + wave * 32;
-    const int w_pmax = kMayPack && t.pk ? t.cb + t.S - 1 : t.cb + min(t.S - 1, t.q0 + wave * 32 + 31);
-    n_w = min(t.n_tiles, w_pmax / kTK + 1);                // steps not wholly above this wavefront's diagonal
+    const int w_pmax = kMayPack && t.pk ? t.cb + t.S - 1 : t.cb + min(t.q_end - 1, t.q0 + wave * 32 + 31);
+    // steps not wholly above this wavefront's diagonal; a wavefront none of whose rows exists (the ragged
+    // last tile of a prompt) has nothing to compute at all
+    const bool any_row = (kMayPack && t.pk) || t.q0 + wave * 32 < t.q_end;
+    n_w = any_row ? min(t.n_tiles, w_pmax / kTK + 1) : 0;
     head_off = (size_t)t.g * 4096;
   };
   enter(cur);
@@ -637,7 +661,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
       rec_next = load_rec(tile_of_f);
       if (tid == 0) pend = atomicAdd(counter, 1);
     }
-    {
+    if (n_w > 0) {
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
