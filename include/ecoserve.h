@@ -342,6 +342,21 @@ int ecoserve_attn_decode_noalloc(int device, const ecoserve_layout* layout, cons
 int ecoserve_probe_hbm_read(int device, size_t bytes, int32_t reps, double* gb_per_s);
 int ecoserve_probe_mfma_bf16(int device, int32_t random_operands, int32_t reps, double* tflop_per_s);
 
+/*
+ * How much vector-ALU work the matrix cores of `device` hide (Section 2.1 counts only the
+ * matrix FLOPs of attention, calling the softmax "a small fraction of the total execution time"; on this
+ * chip the softmax's vector instructions decide how busy the matrix cores can be).  Every wavefront
+ * runs slots of one 32x32x16 bf16 matrix instruction (if with_mfma != 0), fma_per_slot independent
+ * v_fma_f32 and exp_per_slot independent v_exp_f32, register operands only, waves_per_simd (1 or 2)
+ * wavefronts on every SIMD.  *clocks_per_slot = shader clocks one SIMD spends per slot (32 = the
+ * matrix instruction alone; if the vector work were hidden the figure would stay there);
+ * *ghz = the shader clock during the run.  (fma_per_slot, exp_per_slot) must be one of
+ * (0,0) (2,0) (4,0) (8,0) (0,2) (2,2) (4,2), and not (0,0) without the matrix instruction:
+ * else ECOSERVE_EINVAL.  Allocates, synchronises, frees: a measurement helper like the two above.
+ */
+int ecoserve_probe_mfma_valu(int device, int32_t with_mfma, int32_t fma_per_slot, int32_t exp_per_slot,
+                             int32_t waves_per_simd, double* clocks_per_slot, double* ghz);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = [
     "ecoserve_attn_prefill", "ecoserve_attn_decode", "ecoserve_debug_validate", "ecoserve_profile_read",
     "ecoserve_profile_reset", "ecoserve_probe_hbm_read", "ecoserve_probe_mfma_bf16",
     "ecoserve_kv_append_strided", "ecoserve_attn_prefill_strided", "ecoserve_attn_decode_strided",
-    "ecoserve_attn_decode_append", "ecoserve_attn_decode_noalloc",
+    "ecoserve_attn_decode_append", "ecoserve_attn_decode_noalloc", "ecoserve_probe_mfma_valu",
 ]
 
 
@@ -76,6 +76,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.ecoserve_profile_reset.argtypes = [vp]
     lib.ecoserve_probe_hbm_read.argtypes = [ctypes.c_int, ctypes.c_size_t, i32, ctypes.POINTER(ctypes.c_double)]
     lib.ecoserve_probe_mfma_bf16.argtypes = [ctypes.c_int, i32, i32, ctypes.POINTER(ctypes.c_double)]
+    lib.ecoserve_probe_mfma_valu.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_double)]
     return lib
 
 
@@ -122,6 +124,15 @@ def probe_mfma_bf16(random_operands: bool, reps: int = 5, device: int = 0) -> fl
     _check(_lib.ecoserve_probe_mfma_bf16(int(device), int(bool(random_operands)), int(reps), ctypes.byref(rate)),
            "ecoserve_probe_mfma_bf16")
     return rate.value
+
+
+def probe_mfma_valu(with_mfma: bool, fma_per_slot: int, exp_per_slot: int, waves_per_simd: int = 2, device: int = 0):
+    """(shader clocks a SIMD spends per slot of one matrix instruction + the given vector work, shader clock in GHz)."""
+    clocks, ghz = ctypes.c_double(), ctypes.c_double()
+    _check(_lib.ecoserve_probe_mfma_valu(int(device), int(bool(with_mfma)), int(fma_per_slot), int(exp_per_slot),
+                                         int(waves_per_simd), ctypes.byref(clocks), ctypes.byref(ghz)),
+           "ecoserve_probe_mfma_valu")
+    return clocks.value, ghz.value
 
 
 def _ptr(t):

@@ -85,6 +85,63 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mfma_kernel(float* __rest
   if (s == 12345.678f) sink[threadIdx.x] = s;  // keeps the loop alive; practically never taken
 }
 
+// How much vector-ALU work the matrix cores hide: every wavefront runs `iters` rounds of four slots, a slot
+// being one v_mfma_f32_32x32x16_bf16 (if kMfma; four accumulator chains in turn), kFma independent v_fma_f32
+// and kExp independent v_exp_f32, in that order, with the compiler kept from regrouping them.  The online
+// softmax of the prefill kernel is exactly such work beside its matrix instructions.  Each wavefront reports
+// the shader clocks (s_memtime) and the 100 MHz ticks its loop took.
+template <int kFma, int kExp, bool kMfma>
+__global__ __launch_bounds__(kProbeThreads) void probe_slot_kernel(unsigned long long* __restrict__ clocks,
+                                                                    float* __restrict__ sink, int iters) {
+  bf16x8 a[kMfmaChains], b[kMfmaChains];
+  f32x16 acc[kMfmaChains];
+#pragma unroll
+  for (int c = 0; c < kMfmaChains; ++c) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t h = probe_hash(threadIdx.x * 977u + blockIdx.x * 131u + c * 17u + i);
+      a[c][i] = (__bf16)(((int)(h & 0xffff) - 32768) / 16384.0f);
+      b[c][i] = (__bf16)(((int)(h >> 16) - 32768) / 16384.0f);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+  }
+  float x[kFma > 0 ? kFma : 1] = {1.0f}, y[kExp > 0 ? kExp : 1] = {0.f};
+  const float m1 = 0.999f + 1e-6f * (float)(threadIdx.x & 7), m2 = 1e-3f;
+#pragma unroll
+  for (int f = 0; f < kFma; ++f) x[f] = 1.0f + (float)f;
+#pragma unroll
+  for (int e = 0; e < kExp; ++e) y[e] = -0.5f - (float)e;
+  const unsigned long long t0 = __builtin_readcyclecounter(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < kMfmaChains; ++c) {
+      if (kMfma) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c], b[c], acc[c], 0, 0, 0);
+#pragma unroll
+      for (int f = 0; f < kFma; ++f) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[f]) : "v"(m1), "v"(m2));
+#pragma unroll
+      for (int e = 0; e < kExp; ++e) asm volatile("v_exp_f32 %0, %1" : "=v"(y[e]) : "v"(x[kFma > 0 ? e % kFma : 0]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  const unsigned long long t1 = __builtin_readcyclecounter(), w1 = wall_clock64();
+  const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    clocks[2 * wave] = t1 - t0;
+    clocks[2 * wave + 1] = w1 - w0;
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[c][i];
+#pragma unroll
+  for (int f = 0; f < kFma; ++f) s += x[f];
+#pragma unroll
+  for (int e = 0; e < kExp; ++e) s += y[e];
+  if (s == 12345.678f) sink[threadIdx.x] = s;  // keeps the loop alive; practically never taken
+}
+
 struct ProbeTimer {
   hipEvent_t e0 = nullptr, e1 = nullptr;
   hipError_t init() {
@@ -190,6 +247,49 @@ int ecoserve_probe_mfma_bf16(int device, int32_t random_operands, int32_t reps, 
   if (e != hipSuccess) return ECOSERVE_EHIP;
   const double flops = 2.0 * 32 * 32 * 16 * (double)kMfmaChains * kMfmaIters * (kProbeThreads / 64) * wgs;
   *tflop_per_s = flops / (ms * 1e-3) / 1e12;
+  return ECOSERVE_OK;
+}
+
+int ecoserve_probe_mfma_valu(int device, int32_t with_mfma, int32_t fma_per_slot, int32_t exp_per_slot,
+                             int32_t waves_per_simd, double* clocks_per_slot, double* ghz) {
+  using namespace eco;
+  if (!clocks_per_slot || !ghz || waves_per_simd < 1 || waves_per_simd > 2) return ECOSERVE_EINVAL;
+  typedef void (*Kernel)(unsigned long long*, float*, int);
+  Kernel k = nullptr;
+#define ECO_SLOT(F, E)                                                                              \
+  if (fma_per_slot == F && exp_per_slot == E)                                                       \
+    k = with_mfma ? (Kernel)probe_slot_kernel<F, E, true> : (Kernel)probe_slot_kernel<F, E, false>;
+  ECO_SLOT(0, 0) ECO_SLOT(2, 0) ECO_SLOT(4, 0) ECO_SLOT(8, 0) ECO_SLOT(0, 2) ECO_SLOT(2, 2) ECO_SLOT(4, 2)
+#undef ECO_SLOT
+  if (!k || (!with_mfma && fma_per_slot == 0 && exp_per_slot == 0)) return ECOSERVE_EINVAL;
+  int num_cu = 0;
+  if (int st = probe_num_cu(device, &num_cu)) return st;
+  DeviceGuard guard(device);
+  if (!guard.ok) return ECOSERVE_EHIP;
+  const int wgs = num_cu * waves_per_simd, n_waves = wgs * (kProbeThreads / 64), iters = 50000;  // several milliseconds: the clock settles
+  unsigned long long* clocks = nullptr;
+  float* sink = nullptr;
+  if (hipMalloc(&clocks, (size_t)n_waves * 2 * sizeof(unsigned long long)) != hipSuccess ||
+      hipMalloc(&sink, kProbeThreads * sizeof(float)) != hipSuccess) {
+    (void)hipGetLastError();
+    if (clocks) (void)hipFree(clocks);
+    return ECOSERVE_ENOMEM;
+  }
+  std::vector<unsigned long long> host((size_t)n_waves * 2);
+  hipError_t e = hipSuccess;
+  for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {  // the second launch counts
+    hipLaunchKernelGGL(k, dim3(wgs), dim3(kProbeThreads), 0, nullptr, clocks, sink, iters);
+    e = hipDeviceSynchronize();
+  }
+  if (e == hipSuccess) e = hipMemcpy(host.data(), clocks, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+  (void)hipFree(clocks);
+  (void)hipFree(sink);
+  if (e != hipSuccess) { (void)hipGetLastError(); return ECOSERVE_EHIP; }
+  double cyc = 0.0, ticks = 0.0;
+  for (int w = 0; w < n_waves; ++w) cyc += (double)host[2 * w], ticks += (double)host[2 * w + 1];
+  // clocks one SIMD spends per slot: a wavefront's clocks per slot, divided among the wavefronts that share it
+  *clocks_per_slot = cyc / n_waves / ((double)iters * kMfmaChains) / waves_per_simd;
+  *ghz = ticks > 0.0 ? cyc / ticks * 0.1 : 0.0;
   return ECOSERVE_OK;
 }
 
