@@ -88,8 +88,8 @@ int oracle_num_threads(void) {
 }
 
 /*
- * KV-cache append (Section 2.1: "saving the key and value embedding in the
- * memory"; Section 5: fixed-size blocks).
+ * KV-cache append (Section 2.1: the key and value embeddings of processed
+ * tokens are kept in memory for later steps; Section 5: fixed-size blocks).
  *
  * New token i of sequence b lands at absolute position p = ctx_before[b] + i,
  * i.e. in physical block block_table[b][p div bs], slot p mod bs.  The copy is
