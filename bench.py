@@ -767,6 +767,27 @@ def run_machine(E: Env, dec_bytes_layer):
     }
     if dec_bytes_layer:
         m["hbm_read_same_bytes_GBps"] = b.probe_hbm_read(int(dec_bytes_layer) // 8192 * 8192, reps=20)
+    # what a plain device copy moves (read + written bytes per second) at the two sizes kv_append handles in the
+    # prefill workloads: the append is such a pass (every new K/V byte read once and written once) plus a scatter.
+    # As in the benchmark, the source is the same every time and the destination never (a ring of buffers larger
+    # than the 256 MB last-level cache).
+    torch = E.torch
+    for tag, T in (("30b_prefill_batch", 15385), ("8x8192_burst", 65536)):
+        n = T * 8 * 128 * 2          # elements of K and V rows together (bf16)
+        src = torch.empty(n, dtype=torch.bfloat16, device=E.dev).normal_()
+        ring = [torch.empty_like(src) for _ in range(max(3, (1 << 30) // (2 * n) + 1))]
+        for dst in ring[:3]:
+            dst.copy_(src)
+        e0, e1 = E.event(), E.event()
+        reps = max(20, len(ring))
+        e0.record()
+        for i in range(reps):
+            ring[i % len(ring)].copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        m["plain_copy_" + tag] = {"bytes_read_plus_written": 4 * n, "us": us, "GBps": 4 * n / (us * 1e-6) / 1e9}
+        del src, ring
     # how much vector work the matrix cores hide: ns one SIMD spends per slot of one matrix instruction plus the
     # given v_fma_f32 / v_exp_f32 (two wavefronts per SIMD, registers only); the prefill kernel's softmax is
     # about 3.5 plain vector instructions and one v_exp_f32 per matrix instruction
