@@ -25,7 +25,8 @@
 //
 // Per 64-key step the four 16-token cache blocks of K and of V go straight from global
 // memory into LDS (global_load ... lds, 16 bytes per lane, double buffered, one barrier per
-// step); each lane picks the source address of the 16-byte unit that belongs at its LDS
+// step, the eight copies of a wavefront issued one per slot under the step's first matrix
+// instructions); each lane picks the source address of the 16-byte unit that belongs at its LDS
 // position, so the copy also performs the re-tiling.  The cache layouts were chosen so
 // that no transposition is needed anywhere:
 //   K block  [16 units][16 tokens][8 elems]  ->  LDS [unit][64 keys][16 B]:  A operand of
@@ -88,6 +89,14 @@ __device__ __forceinline__ void stage_k(char* kbuf, const char* __restrict__ k_c
   }
 }
 
+// One of the four copies of stage_k (i = 0..3), for callers that spread them out.
+__device__ __forceinline__ void stage_k_one(char* kbuf, const char* __restrict__ k_cache, int idk, size_t head_off,
+                                            size_t blk_stride, int wave, int lane, int i) {
+  const char* ksrc = k_cache + (size_t)idk * blk_stride + head_off + (size_t)(lane & 15) * 16;
+  const int u = 4 * wave + i;
+  __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + u * 256), (lptr_t)(kbuf + u * 1024), 16, 0, 0);
+}
+
 // Same for a V tile: this wavefront copies block `wave` of the tile [id in idv]: octets
 // 2*wave, 2*wave+1; a 1 KiB LDS chunk is 64 consecutive d of one octet, so lane l fetches
 // unit (d = 64 hd + l, half).
@@ -100,6 +109,15 @@ __device__ __forceinline__ void stage_v(char* vbuf, const char* __restrict__ v_c
     for (int hd = 0; hd < 2; ++hd)
       __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + hd * 2048 + hf * 16),
                                        (lptr_t)(vbuf + (2 * wave + hf) * kVOctStride + hd * 1024), 16, 0, 0);
+}
+
+// One of the four copies of stage_v (i = 0..3).
+__device__ __forceinline__ void stage_v_one(char* vbuf, const char* __restrict__ v_cache, int idv, size_t head_off,
+                                            size_t blk_stride, int wave, int lane, int i) {
+  const char* vsrc = v_cache + (size_t)idv * blk_stride + head_off + (size_t)lane * 32;
+  const int hf = i >> 1, hd = i & 1;
+  __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + hd * 2048 + hf * 16),
+                                   (lptr_t)(vbuf + (2 * wave + hf) * kVOctStride + hd * 1024), 16, 0, 0);
 }
 
 // Zero the V entries of keys >= first_bad of a V tile (slots past the end of the sequence
@@ -529,11 +547,25 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     const char* const knext = kbufs + (pj ^ 1) * kKTileBytes;
     const char* const vcur = vbufs + pj * kVTileBytes;
     char* const vnext = vbufs + (pj ^ 1) * kVTileBytes;
-    if constexpr (!is_last) {
-      if (j + 2 < cur.n_tiles) stage_k(kcur, k_cache, next_idk, head_off, blk_stride, wave, lane);
-      stage_v(vnext, v_cache, __builtin_amdgcn_readfirstlane(next_idv), head_off, blk_stride, wave, lane);
+    // The eight global -> LDS copies of a step (K of step j + 2, V of step j + 1) are issued one per slot under
+    // the first matrix instructions of the step instead of in a block before them (2.5% on long prompts); a
+    // wavefront that has nothing to compute in this step issues them at once.  K past the item's last step
+    // re-stages its last block into a buffer that nobody reads before the next item's first step overwrites it.
+    const int idv_s = __builtin_amdgcn_readfirstlane(next_idv);
+    auto copy = [&](int i) {
+      if (i < 4) stage_k_one(kcur, k_cache, next_idk, head_off, blk_stride, wave, lane, i);
+      else stage_v_one(vnext, v_cache, idv_s, head_off, blk_stride, wave, lane, i - 4);
+    };
+    auto next_ids = [&]() {
       next_idk = block_id(cur.bt_row, 4 * (j + 3) + kq, cur.nblk_total());
       next_idv = block_id(cur.bt_row, 4 * (j + 2) + vq, cur.nblk_total());
+    };
+    if constexpr (!is_last) {
+      if (j >= n_w) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copy(i);
+        next_ids();
+      }
     } else if (f_next >= 0) {
       const Item nxt = describe(rec_next, g_next, h_next, block_table, bt_stride);
       stage_first(nxt, rec_next, pj ^ 1);
@@ -587,8 +619,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
         if (s + kAhead < 32) fr[(s + kAhead) % (2 * kAhead)] = frag(s + kAhead);
         const bf16x8 a = fr[s % (2 * kAhead)];
         if (s < 16) {
-          if constexpr (!is_last)
+          if constexpr (!is_last) {
             sn[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s >> 1], s < 2 ? zero : sn[s & 1], 0, 0, 0);
+            if (s >= 1 && s <= 8) copy(s - 1);  // the step's copies ride in slots 1..8, the next block ids in slot 9
+            if (s == 9) next_ids();
+          }
           weight(sc[0], pf0, s);
         } else if (s < 24) {
           const int i = s - 16;
