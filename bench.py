@@ -34,7 +34,7 @@ batches shaped like the paper's chat workloads (`table4_decode`) and the machine
     python bench.py --sweep
 
 times the kernels alone on further batch shapes over a few layer caches each and prints one JSON line
-{"sweep": [...]}: the source of the table in the benchmark spec.
+{"sweep": [...]}.
 """
 from __future__ import annotations
 
