@@ -89,12 +89,20 @@ __device__ __forceinline__ void stage_k(char* kbuf, const char* __restrict__ k_c
   }
 }
 
-// One of the four copies of stage_k (i = 0..3), for callers that spread them out.
-__device__ __forceinline__ void stage_k_one(char* kbuf, const char* __restrict__ k_cache, int idk, size_t head_off,
-                                            size_t blk_stride, int wave, int lane, int i) {
-  const char* ksrc = k_cache + (size_t)idk * blk_stride + head_off + (size_t)(lane & 15) * 16;
-  const int u = 4 * wave + i;
-  __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + u * 256), (lptr_t)(kbuf + u * 1024), 16, 0, 0);
+// One of the four copies of stage_k (I = 0..3), for callers that spread them out.  The instruction's immediate
+// offset is added to the global address and to the LDS address alike, so with the LDS base moved back by the
+// same amount the four copies share one address register pair.
+template <int I>
+__device__ __forceinline__ void stage_k_imm(char* kbuf, const char* ksrc_w, int wave) {
+  __builtin_amdgcn_global_load_lds((gptr_t)ksrc_w, (lptr_t)(kbuf + wave * 4096 + I * (1024 - 256)), 16, I * 256, 0);
+}
+__device__ __forceinline__ void stage_k_one(char* kbuf, const char* ksrc_w, int wave, int i) {
+  switch (i) {
+    case 0: stage_k_imm<0>(kbuf, ksrc_w, wave); break;
+    case 1: stage_k_imm<1>(kbuf, ksrc_w, wave); break;
+    case 2: stage_k_imm<2>(kbuf, ksrc_w, wave); break;
+    default: stage_k_imm<3>(kbuf, ksrc_w, wave); break;
+  }
 }
 
 // Same for a V tile: this wavefront copies block `wave` of the tile [id in idv]: octets
@@ -111,13 +119,19 @@ __device__ __forceinline__ void stage_v(char* vbuf, const char* __restrict__ v_c
                                        (lptr_t)(vbuf + (2 * wave + hf) * kVOctStride + hd * 1024), 16, 0, 0);
 }
 
-// One of the four copies of stage_v (i = 0..3).
-__device__ __forceinline__ void stage_v_one(char* vbuf, const char* __restrict__ v_cache, int idv, size_t head_off,
-                                            size_t blk_stride, int wave, int lane, int i) {
-  const char* vsrc = v_cache + (size_t)idv * blk_stride + head_off + (size_t)lane * 32;
-  const int hf = i >> 1, hd = i & 1;
-  __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + hd * 2048 + hf * 16),
-                                   (lptr_t)(vbuf + (2 * wave + hf) * kVOctStride + hd * 1024), 16, 0, 0);
+// One of the four copies of stage_v (I = 0..3), with the immediate offset as in stage_k_imm.
+template <int I>
+__device__ __forceinline__ void stage_v_imm(char* vbuf, const char* vsrc, int wave) {
+  constexpr int hf = I >> 1, hd = I & 1, imm = hd * 2048 + hf * 16;
+  __builtin_amdgcn_global_load_lds((gptr_t)vsrc, (lptr_t)(vbuf + (2 * wave + hf) * kVOctStride + hd * 1024 - imm), 16, imm, 0);
+}
+__device__ __forceinline__ void stage_v_one(char* vbuf, const char* vsrc, int wave, int i) {
+  switch (i) {
+    case 0: stage_v_imm<0>(vbuf, vsrc, wave); break;
+    case 1: stage_v_imm<1>(vbuf, vsrc, wave); break;
+    case 2: stage_v_imm<2>(vbuf, vsrc, wave); break;
+    default: stage_v_imm<3>(vbuf, vsrc, wave); break;
+  }
 }
 
 // Zero the V entries of keys >= first_bad of a V tile (slots past the end of the sequence
@@ -552,9 +566,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     // wavefront that has nothing to compute in this step issues them at once.  K past the item's last step
     // re-stages its last block into a buffer that nobody reads before the next item's first step overwrites it.
     const int idv_s = __builtin_amdgcn_readfirstlane(next_idv);
+    // one address register pair for the four K copies and one for the four V copies: the pieces differ in the
+    // instructions' immediate offsets (stage_k_imm)
+    const char* const ksrc_w = k_cache + (size_t)next_idk * blk_stride + head_off + (size_t)(lane & 15) * 16 + wave * 1024;
+    const char* const vsrc = v_cache + (size_t)idv_s * blk_stride + head_off + (size_t)lane * 32;
     auto copy = [&](int i) {
-      if (i < 4) stage_k_one(kcur, k_cache, next_idk, head_off, blk_stride, wave, lane, i);
-      else stage_v_one(vnext, v_cache, idv_s, head_off, blk_stride, wave, lane, i - 4);
+      if (i < 4) stage_k_one(kcur, ksrc_w, wave, i);
+      else stage_v_one(vnext, vsrc, wave, i - 4);
     };
     auto next_ids = [&]() {
       next_idk = block_id(cur.bt_row, 4 * (j + 3) + kq, cur.nblk_total());
