@@ -331,7 +331,8 @@ def run_30b(E: Env, args, res: dict):
                        "30b_step" if layers == model.layers and calls == 1 else None)
         r["kernel_ms_per_step"] = k_pre_ms / max(k_pre_n, 1) * calls * layers
         roofs["prefill"] = r
-        a = E.roofline("kv_append_kernel", "hbm", pre_app_bytes_layer / calls, k_papp_ms, k_papp_n)
+        a = E.roofline("kv_append_kernel", "hbm", pre_app_bytes_layer / calls, k_papp_ms, k_papp_n,
+                       "30b_step" if layers == model.layers and calls == 1 else None)
         res["prefill"] = {
             "value": tf, "unit": "TFLOP/s", "ms_per_layer": pre_ms / layers, "phase_ms": pre_ms,
             "frac_of_bf16_peak": tf / acc.PEAK_BF16_TFLOPS,
