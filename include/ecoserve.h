@@ -229,6 +229,23 @@ int ecoserve_debug_validate(ecoserve_ctx* ctx, const int32_t* cu_q, const int32_
                             const int32_t* block_table, int32_t bt_stride, int32_t B);
 
 /*
+ * The work queues' shares of the last ecoserve_attn_prefill launch of this
+ * context (tests and debugging; waits for the device).  The matrix-core
+ * prefill kernel deals its work items to eight queues, one per XCD of the
+ * device; the XCDs do not run equally fast, so from the second launch on the
+ * same batch (same item count) each queue's share of the items follows the
+ * busy time its XCD's workgroups recorded in the launch before (Table 2 and
+ * Section 2.1: prefill attention is the compute-bound phase, a launch is
+ * over when its slowest part is).  Which workgroup computes an item does not
+ * change any result.  shares[q] == 1 for every queue while no measurement
+ * applies: the first launch of a batch, batches below 3072 items, the plain
+ * kernels.
+ *
+ *   shares : host, float[8]; mean 1 over the queues
+ */
+int ecoserve_debug_prefill_queue_shares(ecoserve_ctx* ctx, float* shares);
+
+/*
  * With ECOSERVE_OPT_PROFILE on: synchronise, then return the summed duration
  * (milliseconds) and the number of the bracketed launches of the dominant
  * kernel of `kernel` (ECOSERVE_KERNEL_*) since the last

@@ -28,6 +28,7 @@ EXPORTS = [
     "ecoserve_profile_reset", "ecoserve_probe_hbm_read", "ecoserve_probe_mfma_bf16",
     "ecoserve_kv_append_strided", "ecoserve_attn_prefill_strided", "ecoserve_attn_decode_strided",
     "ecoserve_attn_decode_append", "ecoserve_attn_decode_noalloc", "ecoserve_probe_mfma_valu",
+    "ecoserve_debug_prefill_queue_shares",
 ]
 
 
@@ -72,6 +73,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.ecoserve_attn_decode_noalloc.argtypes = [ctypes.c_int, ctypes.POINTER(Layout), vp, vp, vp, i32p, i32, i32p, vp, vp,
                                                  i32, i32, vp]
     lib.ecoserve_debug_validate.argtypes = [vp, i32p, i32p, i32p, i32, i32]
+    lib.ecoserve_debug_prefill_queue_shares.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.ecoserve_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ecoserve_profile_reset.argtypes = [vp]
     lib.ecoserve_probe_hbm_read.argtypes = [ctypes.c_int, ctypes.c_size_t, i32, ctypes.POINTER(ctypes.c_double)]
@@ -283,6 +285,11 @@ class Context:
     def debug_validate(self, cu_q, ctx_total, block_table):
         return int(_lib.ecoserve_debug_validate(self._h, _ptr(cu_q), _ptr(ctx_total), _ptr(block_table),
                                                 int(block_table.shape[1]), int(ctx_total.numel())))
+
+    def debug_prefill_queue_shares(self):
+        shares = (ctypes.c_float * 8)()
+        _check(_lib.ecoserve_debug_prefill_queue_shares(self._h, shares), "ecoserve_debug_prefill_queue_shares")
+        return [float(x) for x in shares]
 
     def profile_reset(self):
         _check(_lib.ecoserve_profile_reset(self._h), "ecoserve_profile_reset")

@@ -111,6 +111,11 @@ int alloc_fixed_workspace(ecoserve_ctx* c) {
     (void)hipGetLastError();
     return ECOSERVE_ENOMEM;
   }
+  // the plan's header carries state from one prefill launch to the next (queue shares, busy times): none yet
+  if (hipMemset(c->ws_plan, 0, (size_t)kPlanHeaderInts * sizeof(int32_t)) != hipSuccess) {
+    (void)hipGetLastError();
+    return ECOSERVE_EHIP;
+  }
   c->ws_bytes += meta_bytes + plan_bytes;
   return ECOSERVE_OK;
 }
@@ -495,6 +500,19 @@ static int decode_impl(ecoserve_ctx* c, const void* q, int64_t q_row_stride, con
     e = launch_decode_merge(a, ctx_len, split_tokens, c->ws_acc, c->ws_ml, c->ws_splits, s);
     if (e != hipSuccess) return ECOSERVE_EHIP;
   }
+  return ECOSERVE_OK;
+}
+
+int ecoserve_debug_prefill_queue_shares(ecoserve_ctx* c, float* shares) {
+  if (!c || !shares) return ECOSERVE_EINVAL;
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return ECOSERVE_EHIP;
+  if (hipDeviceSynchronize() != hipSuccess) return ECOSERVE_EHIP;
+  // the last launch wrote the set of the parity it ran with; the context's parity has moved on since
+  const int32_t* src = c->ws_plan + kPlanShare0 + kPlanMaxQueues * (c->plan_parity ^ 1);
+  if (hipMemcpy(shares, src, kPlanMaxQueues * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) return ECOSERVE_EHIP;
+  for (int q = 0; q < kPlanMaxQueues; ++q)
+    if (!(shares[q] > 0.f)) shares[q] = 1.f;  // nothing launched yet
   return ECOSERVE_OK;
 }
 

@@ -63,6 +63,8 @@ constexpr int kVTileBytes = 8 * kVOctStride;
 constexpr float kTau = 8.f;                    // lazy-rescale threshold, log2 units
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanBins = 4096;                // weight classes of the plan's counting sort
+constexpr int kBalanceMinItems = 3072;          // batches with fewer items keep equal queues
+constexpr float kShareGain = 2.5f, kShareMin = 0.5f, kShareMax = 1.5f;  // control of the queues' shares
 constexpr int kQueues = 8;                     // work queues (a multiple of 8; more did not help)
 static_assert(kQueues % 8 == 0 && kQueues <= kPlanMaxQueues, "queues come in multiples of the XCD count");
 
@@ -391,10 +393,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     const char* __restrict__ v_cache, const int32_t* __restrict__ block_table, int bt_stride,
     uint16_t* __restrict__ out, float* __restrict__ lse, int32_t* __restrict__ plan, int parity, int Hq, int Hkv, int G, Divisor div_heads, Divisor div_hkv,
     float scale_log2e) {
-  __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes + 16];
+  __shared__ __attribute__((aligned(16))) char smem[2 * kKTileBytes + 2 * kVTileBytes + 16 + 64];
   char* const kbufs = smem;
   char* const vbufs = smem + 2 * kKTileBytes;
   int* const slot = reinterpret_cast<int*>(smem + 2 * kKTileBytes + 2 * kVTileBytes);  // tickets from thread 0
+  int* const qtab = slot + 4;  // [x]: items queue x works through, [8 + x]: items on its own list (wavefront 0 only)
+  const long long t_begin = wall_clock64();
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
@@ -416,21 +420,50 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   // Work items are dealt to kQueues queues (item f belongs to queue f % kQueues) and workgroup w
   // serves queue w % kQueues.  kQueues is a multiple of 8: workgroup ids are dealt round-robin to
   // the 8 XCDs and with eight K/V heads item f reads K/V head f % 8, so an XCD's L2 sees one head's
-  // K/V.  The queues hold the same amount of work to within one item per weight class, and a
-  // workgroup whose queue is empty is done.  Taking from other queues, or from a pool shared by
-  // all, costs more than the imbalance it removes: atomics on one address are served one after the
-  // other, and hundreds of workgroups asking the same counter at the same moment wait tens of
-  // microseconds.
+  // K/V.  The lists hold the same amount of work to within one item per weight class, and a
+  // workgroup whose queue is empty is done.  Taking from other queues when one's own runs dry, or from
+  // a pool shared by all, costs more than the imbalance it removes: atomics on one address are served
+  // one after the other, and hundreds of workgroups asking the same counter at the same moment wait
+  // tens of microseconds.  What does pay is decided before the first ticket: how many items each queue
+  // works through (its quota, below), from the busy times of the launch before.
   const int queue = blockIdx.x % kQueues;
   int* const counter = plan + kPlanCounter0 + kPlanCounterStride * (kQueues * parity + queue);
   // the other counter set is idle (the launch that used it is over): start it for the next launch
   if (blockIdx.x == 0 && threadIdx.x < kQueues)
     plan[kPlanCounter0 + kPlanCounterStride * (kQueues * (parity ^ 1) + threadIdx.x)] =
         2 * (((int)gridDim.x - (int)threadIdx.x + kQueues - 1) / kQueues);
-  auto resolve = [&](int k) -> int {  // ticket k of the own queue -> item, -1 past the end
+  auto resolve0 = [&](int k) -> int {  // ticket k of the own queue -> item of the own list, -1 past its end
     const int f = kQueues * k + queue;
     return f < n_flat ? f : -1;
   };
+  // The same with the queues' quotas (qtab, set up below): a queue that gives items away stops short of the
+  // end of its list, and the lists' ends so left over are dealt, in queue order, to the queues that take
+  // more than their own.  Thread 0 only.
+  auto resolve = [&](int k) -> int {
+    const int quota = qtab[queue], own = qtab[kQueues + queue];
+    if (k < min(quota, own)) return kQueues * k + queue;
+    if (k >= quota) return -1;
+    int p = k - own;  // index into the pool of left-over items
+    for (int x = 0; x < queue; ++x) p += max(qtab[x] - qtab[kQueues + x], 0);
+    for (int d = 0; d < kQueues; ++d) {
+      const int cnt = qtab[kQueues + d] - qtab[d];
+      if (cnt <= 0) continue;
+      if (p < cnt) return kQueues * (qtab[d] + p) + d;
+      p -= cnt;
+    }
+    return -1;
+  };
+  // What the previous launch left behind for this one (the other set): each workgroup's busy time, the
+  // queues' shares and which batch they belong to.  Wavefront 0 asks for them now and uses them below.
+  int busy_sum = 0, prev_items = 0, prev_grid = 0;
+  float share = 0.f;
+  if (wave == 0) {
+    const int32_t* bp = plan + kPlanBusy0 + (parity ^ 1) * kPlanMaxWgs;
+    for (int w = lane; w < (int)gridDim.x && w < kPlanMaxWgs; w += 64) busy_sum += bp[w];
+    share = reinterpret_cast<const float*>(plan)[kPlanShare0 + kQueues * (parity ^ 1) + (lane & 7)];
+    prev_items = plan[kPlanMeta0 + (parity ^ 1)];
+    prev_grid = plan[kPlanMeta0 + 2 + (parity ^ 1)];
+  }
   // item f is query head f % (G Hkv) of tile f / (G Hkv), the K/V head varying fastest
   int tile_of_f, g_of_f, h_of_f;
   auto split = [&](int f) {
@@ -454,14 +487,17 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   if (tid == 0) {
     const int iq = blockIdx.x / kQueues;                                   // index in the queue's crew
     const int nq = ((int)gridDim.x - queue + kQueues - 1) / kQueues;       // size of the crew
-    const int f0 = resolve(iq);
+    const int f0 = resolve0(iq);  // (a queue's quota is never below these two rounds)
     slot[0] = f0;
-    slot[1] = f0 >= 0 ? resolve(iq + nq) : -1;
+    slot[1] = f0 >= 0 ? resolve0(iq + nq) : -1;
   }
   __syncthreads();
   int f_cur = __builtin_amdgcn_readfirstlane(slot[0]);    // the item being computed
   int f_next = __builtin_amdgcn_readfirstlane(slot[1]);   // the one after it (-1: none)
-  if (f_cur < 0) return;
+  if (f_cur < 0) {
+    if (tid == 0 && blockIdx.x < kPlanMaxWgs) plan[kPlanBusy0 + parity * kPlanMaxWgs + blockIdx.x] = 0;
+    return;
+  }
 
   split(f_cur);
   int rec_next = load_rec(tile_of_f);  // record of the next item (here: of the first)
@@ -543,6 +579,47 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   if (kTK > cur.L_total()) {  // the first step already runs past the end of the sequence
     fix_tail(vbufs, cur.L_total(), tid);
     __syncthreads();
+  }
+  // Quotas of the queues.  The XCDs of one device do not run this kernel equally fast (their workgroups end up
+  // to 8% apart, in a pattern that holds from launch to launch), and a launch is over when the slowest is: so a
+  // queue's share of the items follows its XCD's busy time in the previous launch of the same batch (one step
+  // of proportional control per launch; the items that change hands are the lightest ones at the lists' ends,
+  // hence the gain above one).  Which workgroup computes an item does not change its result.
+  if (wave == 0) {
+    // workgroup w runs on XCD w % 8, and lane l summed workgroups l, l + 64, ...: all of XCD l % 8
+    int sum = busy_sum;
+    sum += __shfl_xor(sum, 8);
+    sum += __shfl_xor(sum, 16);
+    sum += __shfl_xor(sum, 32);
+    auto over_queues_i = [&](int v) { v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); return v; };
+    auto over_queues_f = [&](float v) { v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); return v; };
+    const int x = lane & 7;
+    const int crew = ((int)gridDim.x - x + kQueues - 1) / kQueues;
+    const int own = max(n_flat - x + kQueues - 1, 0) / kQueues;
+    const float T = (float)sum / (float)max(crew, 1);
+    const float T_mean = over_queues_f(T) * 0.125f;
+    const bool big = n_flat >= kBalanceMinItems && (int)gridDim.x <= kPlanMaxWgs && gridDim.x % kQueues == 0;
+    const bool same = prev_items == n_flat && prev_grid == (int)gridDim.x;
+    float sh = same && share > 0.f ? share : 1.f;
+    if (big && same && __all(T > 0.f))
+      sh = fminf(kShareMax, fmaxf(kShareMin, sh + kShareGain * (T_mean - T) / T_mean));
+    sh *= 8.f / over_queues_f(sh);
+    int quota = (int)((float)own * sh + 0.5f);
+    const int quota_sum = over_queues_i(quota);
+    if (x == kQueues - 1) quota += n_flat - quota_sum;  // the last queue takes the rounding
+    const bool ok = big && __all(quota >= 2 * crew && own >= 2 * crew);
+    if (!ok) quota = own;
+    if (lane < kQueues) {
+      qtab[lane] = quota;
+      qtab[kQueues + lane] = own;
+      if (blockIdx.x == 0) {
+        reinterpret_cast<float*>(plan)[kPlanShare0 + kQueues * parity + lane] = ok ? sh : 1.f;
+        if (lane == 0) {
+          plan[kPlanMeta0 + parity] = n_flat;
+          plan[kPlanMeta0 + 2 + parity] = (int)gridDim.x;
+        }
+      }
+    }
   }
   int par = 0;  // buffer that holds step 0 of the current item
 
@@ -803,6 +880,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
       for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
     l = 0.f;
   }
+  if (tid == 0 && blockIdx.x < kPlanMaxWgs)
+    plan[kPlanBusy0 + parity * kPlanMaxWgs + blockIdx.x] = (int)(wall_clock64() - t_begin);
 }
 
 // Workgroups of the attention launch: the persistent grid, or fewer if the batch cannot hold that

@@ -21,7 +21,11 @@ constexpr int kPrefillWgsPerCu = 2;   // persistent prefill grid: workgroups per
 constexpr int kPlanMaxQueues = 8;     // prefill plan: most work queues
 constexpr int kPlanCounter0 = 32;     // prefill plan: first queue counter; each counter has a cache line of its own
 constexpr int kPlanCounterStride = 32;
-constexpr int kPlanHeaderInts = kPlanCounter0 + kPlanCounterStride * 2 * kPlanMaxQueues;  // two counter sets, then the records
+constexpr int kPlanShare0 = 8;        // prefill plan: two sets of 8 floats, the queues' shares of the items (0: none yet)
+constexpr int kPlanMeta0 = 24;        // prefill plan: per set, the item count [24 + p] and the grid [26 + p] of the launch that wrote it
+constexpr int kPlanMaxWgs = 1024;     // prefill plan: most workgroups whose busy times a launch records
+constexpr int kPlanBusy0 = kPlanCounter0 + kPlanCounterStride * 2 * kPlanMaxQueues;  // two sets of kPlanMaxWgs busy times (10 ns units)
+constexpr int kPlanHeaderInts = kPlanBusy0 + 2 * kPlanMaxWgs;  // two counter sets, the busy times, then the records
 constexpr int kRecInts = 20;          // prefill plan: int32 fields per query-tile record
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;

@@ -74,6 +74,8 @@ int main() {
   EXPECT(ecoserve_attn_decode_append(nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr, nullptr, 1, nullptr, nullptr,
                                      nullptr, 1, 1, nullptr) == ECOSERVE_EINVAL);
   EXPECT(ecoserve_debug_validate(nullptr, nullptr, nullptr, nullptr, 1, 1) == ECOSERVE_EINVAL);
+  float sh[8];
+  EXPECT(ecoserve_debug_prefill_queue_shares(nullptr, sh) == ECOSERVE_EINVAL);
   double x = 0.0;
   int64_t n = 0;
   EXPECT(ecoserve_profile_read(nullptr, 0, &x, &n) == ECOSERVE_EINVAL);

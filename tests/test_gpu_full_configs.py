@@ -110,6 +110,48 @@ def test_config3_prefill_30b_one_layer_sampled_rows():
     layer.close()
 
 
+def test_config3_prefill_queue_shares_follow_the_xcds_and_change_no_result():
+    """From the second launch on the same batch the prefill kernel deals its items to the eight work queues in
+    shares that follow the busy times its XCDs recorded in the launch before.  Which workgroup computes an item
+    must not change a bit of the result: the first launch (equal shares; the one the test above compares with
+    the oracle row by row) against every later one, with a launch on another batch in between, which sends the
+    shares back to equal."""
+    pb = wl.config3_prefill_30b()
+    model = pb.model
+    layer = Layer(model, pb.num_blocks, pb.B, pb.block_table.shape[1])
+    k, v = _stream(model, pb.T, pb.seed + 4)
+    q = wl.randn((pb.T, model.Hq, model.D), "bf16", pb.seed + 3, device="cuda")
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table, max_new_len=pb.max_q_len)
+    first, first_lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table, max_q_len=pb.max_q_len)
+    shares = layer.ctx.debug_prefill_queue_shares()
+    assert shares == [1.0] * 8, shares  # nothing measured yet
+    # rows sampled against the oracle, as in the test above
+    start, tok, pos = _sample_rows(wl.rng_for(2), pb.q_len)
+    ref, ref_lse = orc.attn_rows(layer.shape, wl.to_bits(q), layer.okc, layer.ovc, pb.block_table, start, tok, pos)
+    compare("prefill, equal shares (sampled rows)", first, ref, "bf16", rows=tok, max_relaxed_share=MAX_RELAXED_SHARE)
+    moved = False
+    for launch in range(1, 9):
+        if launch == 5:
+            # the first three prompts alone: another item count, so the measurements do not apply to it
+            sub_cu = np.asarray(pb.cu_q[:4])
+            nsub = int(sub_cu[-1])
+            o, _ = layer.prefill_gpu(q[:nsub], sub_cu, pb.ctx_before[:3], pb.block_table[:3], max_q_len=pb.max_q_len)
+            assert torch.equal(o.view(torch.int16), first[:nsub].view(torch.int16))
+            assert layer.ctx.debug_prefill_queue_shares() == [1.0] * 8
+            continue
+        out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table, max_q_len=pb.max_q_len)
+        shares = layer.ctx.debug_prefill_queue_shares()
+        say(f"launch {launch}: queue shares " + " ".join(f"{x:.3f}" for x in shares))
+        assert all(0.5 - 1e-6 <= x <= 1.5 + 1e-6 for x in shares) and abs(sum(shares) - 8.0) < 1e-3, shares
+        if launch == 6:
+            assert shares == [1.0] * 8, shares  # the launch before was on another batch
+        moved = moved or any(abs(x - 1.0) > 1e-4 for x in shares)
+        assert torch.equal(out.view(torch.int16), first.view(torch.int16)), f"launch {launch} differs from the first"
+        assert torch.equal(lse.view(torch.int32), first_lse.view(torch.int32)), f"launch {launch}: lse differs"
+    assert moved, "the shares never left 1.0: the measured path did not run"
+    layer.close()
+
+
 @pytest.mark.parametrize("dataset, seed, n_prefill, n_decode, decode_seed", [("alpaca", 32, 512, 1024, 22), ("sharegpt", 31, 64, 512, 21)])
 def test_chat_shaped_prefill_and_decode_batches_in_full(dataset, seed, n_prefill, n_decode, decode_seed):
     """The batches `bench.py --sweep` times for the paper's chat workloads (Table 4; Alpaca: some twenty input
