@@ -190,6 +190,10 @@ int ecoserve_kv_append(ecoserve_ctx* ctx, void* k_cache, void* v_cache, const vo
  *   T / 128 + min(B, T) must not exceed num_blocks / 8 + max_batch (a batch cannot bring more
  *   new tokens than the pool holds; the context's list of query tiles is sized for that), else
  *   ECOSERVE_EINVAL.  The list lives in the context's workspace: see the rule on sharing a context.
+ *   The workspace also carries, from one launch to the next, how long each workgroup was busy and
+ *   the work queues' shares (ecoserve_debug_prefill_queue_shares): they decide which workgroup
+ *   computes which query tile, never a result; out and lse of a call are the same bits whatever
+ *   ran before it.
  */
 int ecoserve_attn_prefill(ecoserve_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
                           const int32_t* cu_q, const int32_t* ctx_before, const int32_t* block_table,
