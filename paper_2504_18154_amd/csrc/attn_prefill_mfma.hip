@@ -455,11 +455,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   };
   // What the previous launch left behind for this one (the other set): each workgroup's busy time, the
   // queues' shares and which batch they belong to.  Wavefront 0 asks for them now and uses them below.
-  int busy_sum = 0, prev_items = 0, prev_grid = 0;
-  float share = 0.f;
+  int prev_items = 0, prev_grid = 0;
+  float busy_sum = 0.f, share = 0.f;  // (a float: 64 busy times of a long launch do not fit an int)
   if (wave == 0) {
     const int32_t* bp = plan + kPlanBusy0 + (parity ^ 1) * kPlanMaxWgs;
-    for (int w = lane; w < (int)gridDim.x && w < kPlanMaxWgs; w += 64) busy_sum += bp[w];
+    for (int w = lane; w < (int)gridDim.x && w < kPlanMaxWgs; w += 64) busy_sum += (float)bp[w];
     share = reinterpret_cast<const float*>(plan)[kPlanShare0 + kQueues * (parity ^ 1) + (lane & 7)];
     prev_items = plan[kPlanMeta0 + (parity ^ 1)];
     prev_grid = plan[kPlanMeta0 + 2 + (parity ^ 1)];
@@ -587,7 +587,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
   // hence the gain above one).  Which workgroup computes an item does not change its result.
   if (wave == 0) {
     // workgroup w runs on XCD w % 8, and lane l summed workgroups l, l + 64, ...: all of XCD l % 8
-    int sum = busy_sum;
+    float sum = busy_sum;
     sum += __shfl_xor(sum, 8);
     sum += __shfl_xor(sum, 16);
     sum += __shfl_xor(sum, 32);
@@ -596,7 +596,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(
     const int x = lane & 7;
     const int crew = ((int)gridDim.x - x + kQueues - 1) / kQueues;
     const int own = max(n_flat - x + kQueues - 1, 0) / kQueues;
-    const float T = (float)sum / (float)max(crew, 1);
+    const float T = sum / (float)max(crew, 1);
     const float T_mean = over_queues_f(T) * 0.125f;
     const bool big = n_flat >= kBalanceMinItems && (int)gridDim.x <= kPlanMaxWgs && gridDim.x % kQueues == 0;
     const bool same = prev_items == n_flat && prev_grid == (int)gridDim.x;
