@@ -131,9 +131,10 @@ __device__ __forceinline__ void process_block(KVFrag& f, const bf16x8 (&qf)[4], 
 // by ~3 us with every piece in its chunk), and some chunks hold a dozen pieces when others hold one.  So
 // that equal chunks are equal work, every (sequence, K/V head) is numbered with kPieceCost units in front
 // of its blocks that stand for that cost and hold no data (in units of a block's time).
-// (from sweeps on five batch shapes: with 2, 3, 4, 6 units 512 sequences of ~400 tokens take 159.6, 154.7,
-// 154.1, 157.0 us; the benchmark batches do not care)
-constexpr int kPieceCost = 4;
+// (a fit of the wavefronts' times against their blocks and pieces gives 2.7 to 3 block times per piece on
+// three batch shapes; with 2, 3, 4 units 1024 sequences of ~120 tokens take 101.1, 99.9, 102.7 us and 512 of
+// ~400 tokens 149.1, 148.5, 149.5 us; the benchmark batches do not care)
+constexpr int kPieceCost = 3;
 
 // Exclusive prefix sums of the per-sequence unit counts (blocks + kPieceCost) into LDS: pre[b] = units
 // per K/V head of sequences 0..b-1, pre[B] = all; lens[b] = context length.  Called by all 256 threads.
@@ -550,8 +551,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
 #pragma unroll
           for (int dt = 0; dt < 8; ++dt) {
             u32x2 w;
-            w[0] = (uint32_t)float_to_bf16_bits(acc[dt][0] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][1] * inv) << 16);
-            w[1] = (uint32_t)float_to_bf16_bits(acc[dt][2] * inv) | ((uint32_t)float_to_bf16_bits(acc[dt][3] * inv) << 16);
+            w[0] = pack_bf16x2(acc[dt][0] * inv, acc[dt][1] * inv);
+            w[1] = pack_bf16x2(acc[dt][2] * inv, acc[dt][3] * inv);
             *reinterpret_cast<u32x2*>(ent + col * 256 + (dt * 16 + 4 * quad) * 2) = w;
           }
           if (quad == 0) *reinterpret_cast<float*>(ent + G * 256 + col * 4) = (m + log2f(l)) * kLn2;
@@ -696,7 +697,7 @@ __device__ __forceinline__ void merge_partials(const float* __restrict__ ws_acc,
     }
   }
   const float inv = 1.f / lsum;
-  const uint32_t packed = (uint32_t)float_to_bf16_bits(o0 * inv) | ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
+  const uint32_t packed = pack_bf16x2(o0 * inv, o1 * inv);
   *reinterpret_cast<uint32_t*>(orow + 2 * lane) = packed;
   if (lse_out && lane == 0) *lse_out = (M + log2f(lsum)) * kLn2;
 }

@@ -208,6 +208,14 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Two fp32 values rounded to nearest even and packed as bf16 (low half first) with the hardware conversion
+// of gfx950; the same bits as float_to_bf16_bits for every finite value.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
 template <typename E>
 struct Elem;
 template <>
