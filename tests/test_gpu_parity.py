@@ -470,6 +470,47 @@ def test_bf16_short_chunk_after_long_prefix():
     layer.close()
 
 
+@pytest.mark.parametrize("heads, n_seq, lo, hi, with_prefix", [((24, 6), 64, 200, 1200, False), ((40, 8), 40, 300, 1500, True),
+                                                               ((16, 1), 24, 800, 2200, False)])
+def test_bf16_prefill_results_do_not_depend_on_the_queue_shares(heads, n_seq, lo, hi, with_prefix):
+    """Batches large enough (3072 work items or more) for the prefill kernel to move its queues' shares of the
+    items with the busy times of the launch before: seven launches on one batch, every one bit for bit the first
+    (whose shares are equal), with and without cached prefixes, for group sizes 4, 5 and 16 (the last with a
+    single K/V head: all queues then share one head's K/V); sampled rows of the first against the oracle."""
+    model = wl.ModelShape(f"h{heads[0]}x{heads[1]}", heads[0], heads[1], 128, 1, "bf16")
+    rng = wl.rng_for(700 + heads[0])
+    q_len = rng.integers(lo, hi, n_seq).astype(np.int32)
+    ctx_before = rng.integers(0, 700, n_seq).astype(np.int32) if with_prefix else None
+    say(f"bf16 prefill, queue shares: {n_seq} prompts of {lo}..{hi} tokens, heads {heads}, prefixes {with_prefix}")
+    pb, layer = _mk(model, q_len, ctx_before=ctx_before, seed=71)
+    if with_prefix:
+        _, kp, vp = _qkv(model, int(pb.ctx_before.sum()), 720)
+        layer.append(kp, vp, wl.cu_from_lengths(pb.ctx_before), np.zeros(pb.B, np.int32), pb.block_table)
+    q, k, v = _qkv(model, pb.T, 710)
+    layer.append(k, v, pb.cu_q, pb.ctx_before, pb.block_table)
+    first, first_lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+    assert layer.ctx.debug_prefill_queue_shares() == [1.0] * 8
+    moved = False
+    for launch in range(1, 7):
+        out, lse = layer.prefill_gpu(q, pb.cu_q, pb.ctx_before, pb.block_table)
+        shares = layer.ctx.debug_prefill_queue_shares()
+        moved = moved or any(abs(x - 1.0) > 1e-4 for x in shares)
+        assert torch.equal(out.view(torch.int16), first.view(torch.int16)), f"launch {launch}: shares {shares}"
+        assert torch.equal(lse.view(torch.int32), first_lse.view(torch.int32)), f"launch {launch}: lse, shares {shares}"
+    say("  shares of the last launch: " + " ".join(f"{x:.3f}" for x in shares))
+    assert moved, "the shares never left 1.0: the batch is too small for the measured path"
+    # a few hundred rows of the first launch against the oracle
+    rows = np.sort(wl.rng_for(73).choice(pb.T, size=min(pb.T, 300), replace=False)).astype(np.int64)
+    seq = np.searchsorted(pb.cu_q, rows, side="right") - 1
+    pos = pb.ctx_before[seq] + (rows - pb.cu_q[seq])
+    start = np.searchsorted(seq, np.arange(pb.B + 1), side="left").astype(np.int32)  # rows of sequence b: start[b] .. start[b+1]-1
+    ref, ref_lse = orc.attn_rows(layer.shape, wl.to_bits(q), layer.okc, layer.ovc, pb.block_table, start,
+                                 rows.astype(np.int32), pos.astype(np.int32))
+    compare("prefill with queue shares (sampled rows)", first, ref, "bf16", rows=rows)
+    compare_lse("prefill with queue shares (sampled rows)", first_lse, ref_lse, "bf16", rows=rows, bf16_row_sum=True)
+    layer.close()
+
+
 def test_bf16_prefill_reuses_the_tile_list_across_layers():
     """Several 'layers' (different caches and queries, the same batch arrays) with the tile list
     built once and reused, against the oracle and bit for bit against the mode that rebuilds it;
