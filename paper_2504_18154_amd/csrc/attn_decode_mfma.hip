@@ -167,10 +167,16 @@ __device__ __forceinline__ void scan_block_counts(int* pre, int* lens, int* wsum
   __syncthreads();
 }
 
+// a / b for a >= 0, b > 0: the numbering's unit counts are 64-bit for the largest pools, but almost always fit
+// 32 bits, where the division is a fraction of the instructions (the values are wavefront-uniform)
+__device__ __forceinline__ long long div_units(long long a, int b) {
+  return (a >> 31) == 0 ? (long long)((uint32_t)a / (uint32_t)b) : a / b;
+}
+
 // Chunk size in units: forced, or the equal share of the persistent grid's wavefronts.
 __device__ __forceinline__ long long chunk_units(long long U, int n_waves, int c_forced) {
   if (c_forced > 0) return c_forced;
-  const long long c = (U + n_waves - 1) / n_waves;
+  const long long c = div_units(U + n_waves - 1, n_waves);
   return c < kMinSplitTokens / kBlockSize ? kMinSplitTokens / kBlockSize : c;
 }
 
@@ -189,7 +195,7 @@ struct Chunking {
   }
   __device__ __forceinline__ int size(int gw) const { return c[(gw >> 2) & 7]; }
   __device__ __forceinline__ int owner(long long u) const {  // the wavefront whose chunk holds unit u
-    const long long r = u / cum[8];
+    const long long r = div_units(u, cum[8]);
     const int off = (int)(u - r * cum[8]);
     int x = 0;
 #pragma unroll
@@ -300,17 +306,24 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_mfma_kernel(
   };
   auto locate = [&](long long u) {
     Piece p;
-    const int key = (int)(u / Hkv);  // largest b with pre[b] <= u / Hkv
-    int lo = 0, hi = B;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (pre[mid] <= key) lo = mid; else hi = mid;
+    const int key = (int)div_units(u, Hkv);  // largest b with pre[b] <= u / Hkv
+    // every lane probes one candidate per round (pre is increasing and pre[lo] <= key throughout, so the lanes
+    // that see pre <= key are the first few): two rounds for the largest batch instead of twelve LDS round trips
+    int lo = 0, n_cand = B;
+    while (n_cand > 1) {
+      const int stride = (n_cand + 63) >> 6;
+      const int idx = lo + lane * stride;
+      const bool le = idx < lo + n_cand && pre[idx] <= key;
+      const int last = __popcll(__ballot(le)) - 1;
+      const int new_lo = lo + last * stride;
+      n_cand = min(stride, lo + n_cand - new_lo);
+      lo = new_lo;
     }
     p.b = lo;
     const int nu = pre[lo + 1] - pre[lo];  // units of one (sequence, head)
     p.nb = nu - kPieceCost;
     const long long seq_u0 = (long long)pre[lo] * Hkv;
-    p.g = (int)((u - seq_u0) / nu);
+    p.g = (int)div_units(u - seq_u0, nu);
     p.seg_u0 = seq_u0 + (long long)p.g * nu;
     p.u_stop = min(u_end, p.seg_u0 + nu);
     p.blk0 = max((int)(u - p.seg_u0) - kPieceCost, 0);
